@@ -1,0 +1,235 @@
+/*
+ * CPU oracle for the Dynamic Sparse Attention (DSA) forward path.
+ *
+ * TEST INFRASTRUCTURE, NOT A PRODUCT PATH.  Only the test-suite, the smoke check and
+ * the benchmark's cpu_baseline leg call this file.  It shares no code with the HIP
+ * library and is deliberately plain: one loop nest per equation, no blocking, no SIMD
+ * intrinsics, no BLAS.  OpenMP only distributes independent (head, unit) problems over
+ * threads; nothing inside a unit is reordered.
+ *
+ * What it computes, and where the paper defines it:
+ *
+ *   step 1  approximate scores  S~[i,j] = sum_c Q~[i,c] K~[j,c]  as exact integers
+ *           (section 3.1: S~ = Q~ K~^T from the low-precision projections).
+ *   step 2  vector-wise only: group score  Sg[g,j] = sum_{r<vec} S~[vec*g+r, j]
+ *           (section 5.1, column-vector sparsity: one decision per vector of `vec`
+ *           consecutive query rows and one key column; the aggregate is their sum).
+ *   step 3  per unit (row or group) keep the `keep` keys with the largest score
+ *           (section 3.1: mask from S~ "determined by top-k searching"; section 4.2 /
+ *           5.2: the same count in every row).  Total order: larger score first, equal
+ *           scores by lower key index first.  The kept indices are emitted ascending.
+ *   step 4  S[i,t] = scale * sum_c Q[i,c] K[j_t,c]   (equation 2 at the kept positions:
+ *           the SDDMM of section 3.4 / 5.1).
+ *   step 5  P[i,t] = exp(S[i,t]-m) / sum_t exp(S[i,t]-m),  m = max_t S[i,t]
+ *           (equation 4: masked entries get -c and so weight 0 -> softmax over kept only).
+ *   step 6  O[i,:] = sum_t P[i,t] V[j_t,:]            (equation 3: the SpMM).
+ *
+ * Floating point is double throughout; Q, K, V arrive as float (bfloat16 inputs are
+ * widened exactly by the caller).  Every function can be restricted to a list of units
+ * / rows so that full-size workloads can be spot-checked.
+ *
+ * Layouts (all row-major, innermost last):
+ *   Qt, Kt  int8   [N, L, k]        N = B*H
+ *   Q, K, V float  [N, L, d]
+ *   idx     int32  [N, L/vec, keep]
+ * "unit id" u in [0, N*L/vec): head n = u / (L/vec), unit-in-head g = u % (L/vec).
+ * "row id"  r in [0, N*L):     head n = r / L, row i = r % L, its unit g = i / vec.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#include <math.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int32_t dsao_num_threads(void)
+{
+#ifdef _OPENMP
+    return (int32_t)omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* keep = round-half-up(ratio * L), clamped to [1, L].  10% of 256 -> 26, of 512 -> 51;
+ * 5% of 2048 -> 102, of 4096 -> 205; 1% of 8192 -> 82. */
+int32_t dsao_keep_from_ratio(int32_t L, double ratio)
+{
+    double x = floor(ratio * (double)L + 0.5);
+    if (x < 1.0) x = 1.0;
+    if (x > (double)L) x = (double)L;
+    return (int32_t)x;
+}
+
+/* Steps 1-2 for one unit: out[j] for j in [0, L). */
+static void unit_scores(const int8_t *Qt, const int8_t *Kt, int64_t L, int64_t k, int64_t vec,
+                        int64_t n, int64_t g, int64_t *out)
+{
+    const int8_t *Kh = Kt + n * L * k;
+    for (int64_t j = 0; j < L; ++j) {
+        int64_t group_sum = 0;
+        for (int64_t r = 0; r < vec; ++r) {
+            const int8_t *q = Qt + (n * L + g * vec + r) * k;
+            int64_t s = 0;                       /* step 1: one approximate score */
+            for (int64_t c = 0; c < k; ++c)
+                s += (int64_t)q[c] * (int64_t)Kh[j * k + c];
+            group_sum += s;                      /* step 2 */
+        }
+        out[j] = group_sum;
+    }
+}
+
+/* Steps 1-2, exported for the pins: scores [n_units, L] as int64. */
+int32_t dsao_approx_scores(const int8_t *Qt, const int8_t *Kt, int32_t N, int32_t L, int32_t k,
+                           int32_t vec, const int64_t *units, int64_t n_units, int64_t *scores)
+{
+    if (!Qt || !Kt || !scores || N < 1 || L < 1 || k < 1 || vec < 1 || L % vec) return 1;
+    int64_t G = L / vec;
+    if (!units) n_units = (int64_t)N * G;
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t t = 0; t < n_units; ++t) {
+        int64_t u = units ? units[t] : t;
+        unit_scores(Qt, Kt, L, k, vec, u / G, u % G, scores + t * (int64_t)L);
+    }
+    return 0;
+}
+
+typedef struct { int64_t score; int32_t j; } scored_key;
+
+/* Total order of step 3: larger score first; equal scores: lower key index first. */
+static int by_score_desc_then_index(const void *a, const void *b)
+{
+    const scored_key *x = (const scored_key *)a, *y = (const scored_key *)b;
+    if (x->score != y->score) return x->score > y->score ? -1 : 1;
+    return (x->j > y->j) - (x->j < y->j);
+}
+
+static int by_int32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* Steps 1-3: idx [n_units, keep], each list ascending. */
+int32_t dsao_predict_mask(const int8_t *Qt, const int8_t *Kt, int32_t N, int32_t L, int32_t k,
+                          int32_t vec, int32_t keep, const int64_t *units, int64_t n_units,
+                          int32_t *idx)
+{
+    if (!Qt || !Kt || !idx || N < 1 || L < 1 || k < 1 || vec < 1 || L % vec) return 1;
+    if (keep < 1 || keep > L) return 1;
+    int64_t G = L / vec;
+    if (!units) n_units = (int64_t)N * G;
+    int failed = 0;
+#pragma omp parallel
+    {
+        int64_t *sc = (int64_t *)malloc(sizeof(int64_t) * (size_t)L);
+        scored_key *keys = (scored_key *)malloc(sizeof(scored_key) * (size_t)L);
+        if (!sc || !keys) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t t = 0; t < n_units; ++t) {
+            if (!sc || !keys) continue;
+            int64_t u = units ? units[t] : t;
+            unit_scores(Qt, Kt, L, k, vec, u / G, u % G, sc);
+            for (int32_t j = 0; j < L; ++j) { keys[j].score = sc[j]; keys[j].j = j; }
+            qsort(keys, (size_t)L, sizeof(scored_key), by_score_desc_then_index);
+            int32_t *out = idx + t * (int64_t)keep;
+            for (int32_t a = 0; a < keep; ++a) out[a] = keys[a].j;
+            qsort(out, (size_t)keep, sizeof(int32_t), by_int32);
+        }
+        free(sc);
+        free(keys);
+    }
+    return failed;
+}
+
+/* Step 4 for the rows listed (all rows if rows == NULL): S [n_rows, keep] in double.
+ * idx is the full [N, L/vec, keep] tensor. */
+int32_t dsao_sddmm(const float *Q, const float *K, const int32_t *idx, int32_t N, int32_t L,
+                   int32_t d, int32_t vec, int32_t keep, double scale, const int64_t *rows,
+                   int64_t n_rows, double *S)
+{
+    if (!Q || !K || !idx || !S || N < 1 || L < 1 || d < 1 || vec < 1 || L % vec || keep < 1) return 1;
+    int64_t G = L / vec;
+    if (!rows) n_rows = (int64_t)N * L;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t t = 0; t < n_rows; ++t) {
+        int64_t r = rows ? rows[t] : t;
+        int64_t n = r / L, i = r % L, g = i / vec;
+        const float *q = Q + r * d;
+        const int32_t *list = idx + (n * G + g) * keep;
+        for (int32_t a = 0; a < keep; ++a) {
+            const float *kr = K + (n * L + list[a]) * (int64_t)d;
+            double acc = 0.0;
+            for (int32_t c = 0; c < d; ++c) acc += (double)q[c] * (double)kr[c];
+            S[t * keep + a] = scale * acc;
+        }
+    }
+    return 0;
+}
+
+/* Step 5 on n_rows lists of `keep` scores. */
+int32_t dsao_sparse_softmax(const double *S, int64_t n_rows, int32_t keep, double *P)
+{
+    if (!S || !P || keep < 1 || n_rows < 0) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n_rows; ++t) {
+        const double *s = S + t * keep;
+        double *p = P + t * keep;
+        double m = s[0];
+        for (int32_t a = 1; a < keep; ++a) if (s[a] > m) m = s[a];
+        double z = 0.0;
+        for (int32_t a = 0; a < keep; ++a) { p[a] = exp(s[a] - m); z += p[a]; }
+        for (int32_t a = 0; a < keep; ++a) p[a] = p[a] / z;
+    }
+    return 0;
+}
+
+/* Step 6 for the rows listed: O [n_rows, d] in double.  P is [n_rows, keep]. */
+int32_t dsao_spmm(const double *P, const int32_t *idx, const float *V, int32_t N, int32_t L,
+                  int32_t d, int32_t vec, int32_t keep, const int64_t *rows, int64_t n_rows,
+                  double *O)
+{
+    if (!P || !idx || !V || !O || N < 1 || L < 1 || d < 1 || vec < 1 || L % vec || keep < 1) return 1;
+    int64_t G = L / vec;
+    if (!rows) n_rows = (int64_t)N * L;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t t = 0; t < n_rows; ++t) {
+        int64_t r = rows ? rows[t] : t;
+        int64_t n = r / L, i = r % L, g = i / vec;
+        const int32_t *list = idx + (n * G + g) * keep;
+        double *o = O + t * d;
+        for (int32_t c = 0; c < d; ++c) o[c] = 0.0;
+        for (int32_t a = 0; a < keep; ++a) {
+            const float *vr = V + (n * L + list[a]) * (int64_t)d;
+            double p = P[t * keep + a];
+            for (int32_t c = 0; c < d; ++c) o[c] += p * (double)vr[c];
+        }
+    }
+    return 0;
+}
+
+/* Steps 4-6 chained for the rows listed, given idx.  S, P may be NULL. */
+int32_t dsao_masked_attention(const float *Q, const float *K, const float *V, const int32_t *idx,
+                              int32_t N, int32_t L, int32_t d, int32_t vec, int32_t keep,
+                              double scale, const int64_t *rows, int64_t n_rows, double *O,
+                              double *S_out, double *P_out)
+{
+    if (!rows) n_rows = (int64_t)N * L;
+    if (n_rows < 0 || keep < 1) return 1;
+    double *S = S_out ? S_out : (double *)malloc(sizeof(double) * (size_t)n_rows * keep);
+    double *P = P_out ? P_out : (double *)malloc(sizeof(double) * (size_t)n_rows * keep);
+    int32_t rc = 1;
+    if (S && P) {
+        rc = dsao_sddmm(Q, K, idx, N, L, d, vec, keep, scale, rows, n_rows, S);
+        if (!rc) rc = dsao_sparse_softmax(S, n_rows, keep, P);
+        if (!rc) rc = dsao_spmm(P, idx, V, N, L, d, vec, keep, rows, n_rows, O);
+    }
+    if (!S_out) free(S);
+    if (!P_out) free(P);
+    return rc;
+}

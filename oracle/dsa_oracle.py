@@ -1,0 +1,200 @@
+"""ctypes front end of the CPU oracle (`dsa_oracle.c`).
+
+TEST INFRASTRUCTURE, NOT A PRODUCT PATH: only tests, the smoke check and the
+benchmark's cpu_baseline leg may import this.  It imports nothing from the HIP
+package.  Arrays in, arrays out; all arithmetic lives in the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "dsa_oracle.c"
+_LIB = _HERE / "libdsa_oracle.so"
+_lib = None
+
+CFLAGS = ["-O3", "-march=native", "-fopenmp", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> Path:
+    """Compile the oracle with gcc.  Rebuilds when the source is newer than the library."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(f".tmp{os.getpid()}.so")
+        subprocess.run(["gcc", *CFLAGS, str(_SRC), "-o", str(tmp), "-lm"], check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(str(_LIB))
+        i32, i64, f64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
+        lib.dsao_num_threads.restype = i32
+        lib.dsao_num_threads.argtypes = []
+        lib.dsao_keep_from_ratio.restype = i32
+        lib.dsao_keep_from_ratio.argtypes = [i32, f64]
+        lib.dsao_approx_scores.restype = i32
+        lib.dsao_approx_scores.argtypes = [vp, vp, i32, i32, i32, i32, vp, i64, vp]
+        lib.dsao_predict_mask.restype = i32
+        lib.dsao_predict_mask.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, i64, vp]
+        lib.dsao_sddmm.restype = i32
+        lib.dsao_sddmm.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f64, vp, i64, vp]
+        lib.dsao_sparse_softmax.restype = i32
+        lib.dsao_sparse_softmax.argtypes = [vp, i64, i32, vp]
+        lib.dsao_spmm.restype = i32
+        lib.dsao_spmm.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, vp]
+        lib.dsao_masked_attention.restype = i32
+        lib.dsao_masked_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, f64,
+                                              vp, i64, vp, vp, vp]
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _arr(a, dtype, ndim=None):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    if ndim is not None and a.ndim != ndim:
+        raise ValueError(f"expected {ndim} dims, got shape {a.shape}")
+    return a
+
+
+def _sel(sel):
+    if sel is None:
+        return None, 0
+    s = _arr(sel, np.int64, 1)
+    return s, s.size
+
+
+def num_threads() -> int:
+    return int(_load().dsao_num_threads())
+
+
+def keep_from_ratio(L: int, ratio: float) -> int:
+    return int(_load().dsao_keep_from_ratio(L, ratio))
+
+
+def _flat_heads(x, dtype):
+    """[B,H,L,c] or [N,L,c] -> contiguous [N,L,c]."""
+    x = np.ascontiguousarray(x, dtype=dtype)
+    if x.ndim == 4:
+        x = x.reshape(x.shape[0] * x.shape[1], x.shape[2], x.shape[3])
+    if x.ndim != 3:
+        raise ValueError(f"expected [B,H,L,c] or [N,L,c], got {x.shape}")
+    return x
+
+
+def approx_scores(Qt, Kt, vec=1, units=None) -> np.ndarray:
+    """Steps 1-2.  int64 [n_units, L]."""
+    Qt, Kt = _flat_heads(Qt, np.int8), _flat_heads(Kt, np.int8)
+    N, L, k = Qt.shape
+    assert Kt.shape == Qt.shape
+    u, nu = _sel(units)
+    if u is None:
+        nu = N * (L // vec)
+    out = np.empty((nu, L), dtype=np.int64)
+    rc = _load().dsao_approx_scores(_p(Qt), _p(Kt), N, L, k, vec, _p(u), nu, _p(out))
+    if rc:
+        raise ValueError("dsao_approx_scores: bad arguments")
+    return out
+
+
+def predict_mask(Qt, Kt, keep, vec=1, units=None) -> np.ndarray:
+    """Steps 1-3.  int32 [n_units, keep] (all units of all heads, flattened, if units is None)."""
+    Qt, Kt = _flat_heads(Qt, np.int8), _flat_heads(Kt, np.int8)
+    N, L, k = Qt.shape
+    assert Kt.shape == Qt.shape
+    u, nu = _sel(units)
+    if u is None:
+        nu = N * (L // vec)
+    out = np.empty((nu, keep), dtype=np.int32)
+    rc = _load().dsao_predict_mask(_p(Qt), _p(Kt), N, L, k, vec, keep, _p(u), nu, _p(out))
+    if rc:
+        raise ValueError("dsao_predict_mask: bad arguments")
+    return out
+
+
+def _idx_full(idx, N, L, vec):
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    keep = idx.shape[-1]
+    idx = idx.reshape(-1, keep)
+    if idx.shape[0] != N * (L // vec):
+        raise ValueError("idx must cover every unit of every head")
+    if idx.size and (idx.min() < 0 or idx.max() >= L):
+        raise ValueError("idx out of range")
+    return idx, keep
+
+
+def sddmm(Q, K, idx, scale, vec=1, rows=None) -> np.ndarray:
+    """Step 4.  float64 [n_rows, keep]."""
+    Q, K = _flat_heads(Q, np.float32), _flat_heads(K, np.float32)
+    N, L, d = Q.shape
+    idx, keep = _idx_full(idx, N, L, vec)
+    r, nr = _sel(rows)
+    if r is None:
+        nr = N * L
+    S = np.empty((nr, keep), dtype=np.float64)
+    rc = _load().dsao_sddmm(_p(Q), _p(K), _p(idx), N, L, d, vec, keep, float(scale), _p(r), nr, _p(S))
+    if rc:
+        raise ValueError("dsao_sddmm: bad arguments")
+    return S
+
+
+def sparse_softmax(S) -> np.ndarray:
+    """Step 5.  float64, same shape as S ([..., keep])."""
+    S = np.ascontiguousarray(S, dtype=np.float64)
+    keep = S.shape[-1]
+    P = np.empty_like(S)
+    rc = _load().dsao_sparse_softmax(_p(S), S.size // keep, keep, _p(P))
+    if rc:
+        raise ValueError("dsao_sparse_softmax: bad arguments")
+    return P
+
+
+def spmm(P, idx, V, vec=1, rows=None) -> np.ndarray:
+    """Step 6.  float64 [n_rows, d]."""
+    V = _flat_heads(V, np.float32)
+    N, L, d = V.shape
+    idx, keep = _idx_full(idx, N, L, vec)
+    r, nr = _sel(rows)
+    if r is None:
+        nr = N * L
+    P = np.ascontiguousarray(P, dtype=np.float64).reshape(nr, keep)
+    O = np.empty((nr, d), dtype=np.float64)
+    rc = _load().dsao_spmm(_p(P), _p(idx), _p(V), N, L, d, vec, keep, _p(r), nr, _p(O))
+    if rc:
+        raise ValueError("dsao_spmm: bad arguments")
+    return O
+
+
+def masked_attention(Q, K, V, idx, scale, vec=1, rows=None, return_sp=False):
+    """Steps 4-6 given idx.  float64 O [n_rows, d] (and S, P [n_rows, keep])."""
+    Q, K, V = (_flat_heads(x, np.float32) for x in (Q, K, V))
+    N, L, d = Q.shape
+    idx, keep = _idx_full(idx, N, L, vec)
+    r, nr = _sel(rows)
+    if r is None:
+        nr = N * L
+    O = np.empty((nr, d), dtype=np.float64)
+    S = np.empty((nr, keep), dtype=np.float64) if return_sp else None
+    P = np.empty((nr, keep), dtype=np.float64) if return_sp else None
+    rc = _load().dsao_masked_attention(_p(Q), _p(K), _p(V), _p(idx), N, L, d, vec, keep,
+                                       float(scale), _p(r), nr, _p(O), _p(S), _p(P))
+    if rc:
+        raise ValueError("dsao_masked_attention: bad arguments")
+    return (O, S, P) if return_sp else O
+
+
+def attention_fwd(Q, K, V, Qt, Kt, keep, scale, vec=1):
+    """Whole path, all rows.  Returns (O float64 [N*L, d], idx int32 [N*L/vec, keep])."""
+    idx = predict_mask(Qt, Kt, keep, vec)
+    return masked_attention(Q, K, V, idx, scale, vec), idx
