@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the DSA attention forward on one MI355X.
+
+Workload: the long-sequence configuration the headline metric is quoted on (B=2, H=8, L=4096,
+d=64, bf16, k=32 int8 projections, keep 5% = 205 keys), run fine-grained and vector-wise (8x1)
+side by side on the same seeded synthetic tensors.  One step = one fine-grained forward plus
+one vector-wise forward through dsa_attention_fwd (mask prediction, SDDMM, softmax over kept
+entries, SpMM), inputs resident in HBM.  value = heads*sequences processed per second over
+both passes.
+
+Prints ONE JSON line with the throughput, the roofline figures of the dominant kernel (the
+gather-bound attention kernel of the fine-grained pass) and the CPU oracle timed on the host
+cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+
+# HBM traffic of one launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this command (see profiles/); None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def gather_bytes(cfg) -> int:
+    """Algorithmic bytes of SDDMM + softmax + SpMM: every kept K row and V row is read once per
+    selection unit, Q read once, O written once (fp32), the index lists read once."""
+    e = 4 if cfg.dtype == "f32" else 2
+    G = cfg.units
+    rows = cfg.N * cfg.L
+    return 2 * G * cfg.keep * cfg.d * e + rows * cfg.d * e + rows * cfg.d * 4 + G * cfg.keep * 4
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (every head*sequence is an independent problem and "
+              "would shard over GPUs with no exchange step, but no multi-GPU path is built); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import dsa_inputs as di
+    import paper_2110_11299_amd as pkg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    pkg.binding.lib()   # fails loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+
+    cf, cv = di.CONFIGS["C4f"], di.CONFIGS["C4v"]
+    x = di.make_inputs(cf)
+
+    def dev(name):
+        return torch.from_numpy(x.storage(name).view(np.int16)).cuda().view(torch.bfloat16)
+
+    Q, K, V = dev("Q"), dev("K"), dev("V")
+    Qt, Kt = torch.from_numpy(x.Qt).cuda(), torch.from_numpy(x.Kt).cuda()
+    passes = []
+    for cfg in (cf, cv):
+        sh = pkg.make_shape(cfg.B, cfg.H, cfg.L, cfg.d, cfg.k, cfg.keep, cfg.vec, pkg.DSA_BF16, float(cfg.scale))
+        passes.append(dict(cfg=cfg, sh=sh,
+                           O=torch.empty((cfg.B, cfg.H, cfg.L, cfg.d), dtype=torch.float32, device="cuda"),
+                           idx=torch.empty((cfg.B, cfg.H, cfg.L // cfg.vec, cfg.keep), dtype=torch.int32, device="cuda"),
+                           ws=pkg.binding.alloc_workspace(sh)))
+
+    def step():
+        for p in passes:
+            pkg.dsa_attention_fwd(p["sh"], Q, K, V, Qt, Kt, O=p["O"], idx_out=p["idx"], ws=p["ws"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    heads_seqs = sum(p["cfg"].N for p in passes)
+    value = heads_seqs / (ms_per_step * 1e-3)
+
+    # Per-kernel durations, same kernels and launch shapes, HIP events on the launch stream.
+    def timed(fn, reps):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        evs[0].record()
+        for i in range(reps):
+            fn()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        return sum(evs[i].elapsed_time(evs[i + 1]) for i in range(reps)) / reps   # ms
+
+    reps = max(args.steps, 5)
+    stages = {}
+    for p in passes:
+        name = p["cfg"].name
+        stages[name] = dict(
+            predict_ms=timed(lambda: pkg.dsa_predict_mask(p["sh"], Qt, Kt, idx=p["idx"], ws=p["ws"]), reps),
+            attention_ms=timed(lambda: pkg.dsa_masked_attention(p["sh"], Q, K, V, p["idx"], O=p["O"]), reps),
+            fwd_ms=timed(lambda: pkg.dsa_attention_fwd(p["sh"], Q, K, V, Qt, Kt, O=p["O"], idx_out=p["idx"],
+                                                       ws=p["ws"]), reps))
+    sh_f = passes[0]["sh"]
+    rowmax = torch.empty((cf.B, cf.H, cf.L), dtype=torch.int32, device="cuda")
+    contraction_ms = timed(lambda: pkg.dsa_approx_rowmax(sh_f, Qt, Kt, rowmax=rowmax), reps)
+
+    int8_ops = 2.0 * cf.N * cf.L * cf.L * cf.k
+    for name, p in zip(stages, passes):
+        cfg = p["cfg"]
+        st = stages[name]
+        st["heads_seqs_per_s"] = cfg.N / (st["fwd_ms"] * 1e-3)
+        st["attention_gather_GBs"] = gather_bytes(cfg) / (st["attention_ms"] * 1e-3) / 1e9
+        st["attention_frac_hbm"] = st["attention_gather_GBs"] / HBM_PEAK_GBS
+        st["predict_int8_TOPS"] = int8_ops / (st["predict_ms"] * 1e-3) / 1e12
+        st["predict_frac_int8"] = st["predict_int8_TOPS"] / INT8_PEAK_TOPS
+    contraction = dict(kernel="dsa_approx_rowmax", ms=contraction_ms,
+                       int8_TOPS=int8_ops / (contraction_ms * 1e-3) / 1e12)
+    contraction["frac_int8"] = contraction["int8_TOPS"] / INT8_PEAK_TOPS
+
+    dom = stages["C4f"]
+    roofline = dict(kernel="attention_rows (fine-grained SDDMM+softmax+SpMM)", bound="hbm",
+                    achieved=dom["attention_gather_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=dom["attention_frac_hbm"], traffic=MEASURED_TRAFFIC_BYTES,
+                    algorithmic_bytes=gather_bytes(cf), avg_launch_ms=dom["attention_ms"])
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import dsa_oracle
+        heads = 4
+        sl = slice(0, heads)
+        Qf, Kf, Vf = (a.reshape(cf.N, cf.L, cf.d)[sl] for a in (x.Q, x.K, x.V))
+        Qtf, Ktf = (a.reshape(cf.N, cf.L, cf.k)[sl] for a in (x.Qt, x.Kt))
+        dsa_oracle.predict_mask(Qtf[:1, :64], Ktf[:1, :64], 4, 1)   # load the library outside the timing
+        t0 = time.perf_counter()
+        for cfg in (cf, cv):
+            dsa_oracle.attention_fwd(Qf, Kf, Vf, Qtf, Ktf, cfg.keep, cfg.scale, cfg.vec)
+        t_cpu = time.perf_counter() - t0
+        cpu_baseline = dict(value=2 * heads / t_cpu, unit="heads*seqs/s", cores=dsa_oracle.num_threads(),
+                            kind="oracle", seconds=t_cpu,
+                            sample=f"first {heads} of {cf.N} heads*seqs of the same tensors, fine-grained pass "
+                                   f"then vector-wise pass, plain C oracle with OpenMP over units")
+
+    out = dict(metric="DSA attn fwd heads*seqs/sec at L=4096, keep 5%", value=value, unit="heads*seqs/s",
+               n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True,
+               scaling="weak", vs_baseline=None, dtype="f32",
+               data="synthetic",
+               config=dict(workload="C4 long-sequence DSA: B=2 H=8 L=4096 d=64 bf16, k=32 int8, keep 205 (5%), "
+                                    "one fine-grained pass + one vector-wise 8x1 pass per step",
+                           storage="Q,K,V bf16; Q~,K~ int8; O fp32", arithmetic="int8 x int8 -> int32 scores; "
+                           "fp32 dot products, softmax and accumulation",
+                           heads_seqs_per_step=heads_seqs, seed=cf.seed),
+               roofline=roofline, cpu_baseline=cpu_baseline, stages=stages, contraction=contraction,
+               host_cores=len(os.sched_getaffinity(0)), device=torch.cuda.get_device_name(0))
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,127 @@
+/*
+ * dsa.h -- C ABI of the MI355X (gfx950) Dynamic Sparse Attention forward path.
+ *
+ * The path is the per-layer attention forward of "Transformer Acceleration with Dynamic
+ * Sparse Attention" (arXiv 2110.11299):
+ *
+ *   (a) approximate scores  S~ = Q~ K~^T  from reduced-dimension, int8 query / key
+ *       projections (section 3.1, equation 5 and the paragraph after it; "essentially a
+ *       low-precision GEMM", section 3.4);
+ *   (b) a sparse mask M with the same number of kept keys in every row, found by top-k over
+ *       S~ (section 3.1; section 4.2 "keep 10% of the attention weights in each row";
+ *       section 5.2 row-wise constraint), at fine-grained or column-vector granularity
+ *       (section 5.1, figure 9);
+ *   (c) exact attention at the kept positions only: SDDMM  S = Q K^T|_M  (equation 2),
+ *       softmax over the kept entries (equation 4: masked entries get weight 0), and
+ *       SpMM  Z = A V  (equation 3) -- section 3.4 and section 5.1.
+ *
+ * Conventions for every entry point
+ * ---------------------------------
+ *  - Every data pointer is a DEVICE pointer to memory the caller owns (allocated, for
+ *    instance, by PyTorch).  The library allocates nothing, frees nothing and never
+ *    synchronises: kernels are enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream) and the call returns.  Inputs are only read, outputs are fully
+ *    overwritten, there is no state between calls.  Pointers must be 16-byte aligned.
+ *  - Tensors are contiguous, innermost dimension last:
+ *        Q, K, V   [B, H, L, d]   float (DSA_F32) or bfloat16 bit patterns (DSA_BF16)
+ *        Qt, Kt    [B, H, L, k]   int8, the quantised projections Q~, K~
+ *        idx       [B, H, L/vec, keep]  int32: the mask in ELL form.  Entry (b,h,u,:) lists,
+ *                  ascending, the kept key positions of selection unit u: query row u when
+ *                  vec = 1, query rows [vec*u, vec*u+vec) when vec = 8 (they share a list).
+ *        S, P      [B, H, L, keep]  float: exact scores / attention weights at the kept
+ *                  positions of each query row, in the order of its unit's list
+ *        O         [B, H, L, d]   float
+ *  - Selection rule (b): unit u keeps the `keep` keys j with the largest score, where the
+ *    score is S~[u, j] (vec = 1) or the sum of S~[i, j] over the unit's vec rows (vec = 8),
+ *    compared as signed integers; among equal scores the lower j wins.  The result is unique,
+ *    so idx is reproducible bit for bit.
+ *  - Argument checking happens on the host before anything is launched; a call that returns
+ *    an error has launched nothing.  Errors never cross the ABI as exceptions or aborts.
+ */
+#ifndef DSA_H
+#define DSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DSA_OK = 0,
+    DSA_ERR_NULL = 1,        /* a required pointer is NULL                                    */
+    DSA_ERR_SHAPE = 2,       /* a dimension is out of range (see dsa_shape)                   */
+    DSA_ERR_UNSUPPORTED = 3, /* valid in principle, not built: vec, k, d, dtype, size limits  */
+    DSA_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned                              */
+    DSA_ERR_WORKSPACE = 5,   /* workspace missing or smaller than dsa_workspace_bytes()       */
+    DSA_ERR_HIP = 6          /* the HIP runtime refused a launch                              */
+} dsa_status;
+
+typedef enum { DSA_F32 = 0, DSA_BF16 = 1 } dsa_dtype;
+
+/* Problem statement of one attention layer (section 2.1 for B, H, L, d; section 3.1 for k;
+ * section 4.2 for keep; section 5.1 for vec). */
+typedef struct {
+    int32_t B, H;   /* batch, heads: B*H independent problems, each >= 1                      */
+    int32_t L;      /* sequence length, 1 <= L <= 65536, L % vec == 0                         */
+    int32_t d;      /* head dimension of Q, K, V: 64 or 128                                   */
+    int32_t k;      /* projection dimension of Qt, Kt: a multiple of 16, 16 <= k <= 128       */
+    int32_t keep;   /* kept keys per selection unit, 1 <= keep <= L                           */
+    int32_t vec;    /* mask granularity in query rows: 1 (fine-grained) or 8 (vector-wise)    */
+    int32_t dtype;  /* dsa_dtype of Q, K, V                                                   */
+    float scale;    /* factor on the exact scores before softmax; 1/sqrt(d) in equation 2     */
+} dsa_shape;
+
+/* Kept count for a keep ratio: floor(ratio*L + 0.5) clamped to [1, L] ("keep 10%",
+ * section 4.2).  Host only; no device work. */
+int32_t dsa_keep_from_ratio(int32_t L, double ratio);
+
+/* Bytes of device scratch that dsa_predict_mask / dsa_attention_fwd need for this shape
+ * (0 is possible).  Returns 0 for an invalid shape. */
+size_t dsa_workspace_bytes(const dsa_shape *shape);
+
+/* Steps (a)+(b): approximate scores and top-k mask (section 3.1).  Reads Qt, Kt; writes idx.
+ * S~ is never stored.  `ws` / `ws_bytes`: device scratch of at least dsa_workspace_bytes(). */
+dsa_status dsa_predict_mask(const dsa_shape *shape, const int8_t *Qt, const int8_t *Kt,
+                            int32_t *idx, void *ws, size_t ws_bytes, void *stream);
+
+/* Step (c1), SDDMM (equation 2 at the kept positions; section 3.4):
+ * S[b,h,i,t] = scale * sum_c Q[b,h,i,c] * K[b,h,idx[b,h,i/vec,t],c]. */
+dsa_status dsa_sddmm(const dsa_shape *shape, const void *Q, const void *K, const int32_t *idx,
+                     float *S, void *stream);
+
+/* Step (c2), softmax over the kept entries of each row (equation 4; section 5.1 "Sparse
+ * Softmax Computation").  P may alias S. */
+dsa_status dsa_sparse_softmax(const dsa_shape *shape, const float *S, float *P, void *stream);
+
+/* Step (c3), SpMM (equation 3; section 3.4):
+ * O[b,h,i,:] = sum_t P[b,h,i,t] * V[b,h,idx[b,h,i/vec,t],:]. */
+dsa_status dsa_spmm(const dsa_shape *shape, const float *P, const int32_t *idx, const void *V,
+                    float *O, void *stream);
+
+/* Steps (c1)-(c3) in one kernel given the mask: S and P stay on chip. */
+dsa_status dsa_masked_attention(const dsa_shape *shape, const void *Q, const void *K,
+                                const void *V, const int32_t *idx, float *O, void *stream);
+
+/* The whole path (a)-(c) (figure 2(b)): predict the mask, then attend at the kept positions.
+ * idx_out may be NULL; if not, it also receives the mask.  When idx_out is NULL the mask
+ * lives in `ws`. */
+dsa_status dsa_attention_fwd(const dsa_shape *shape, const void *Q, const void *K, const void *V,
+                             const int8_t *Qt, const int8_t *Kt, float *O, int32_t *idx_out,
+                             void *ws, size_t ws_bytes, void *stream);
+
+/* Step (a) alone with the smallest possible consumer, for measuring the int8 contraction:
+ * rowmax[b,h,i] = max_j S~[b,h,i,j] (int32 [B,H,L]).  Uses B, H, L, k of the shape only. */
+dsa_status dsa_approx_rowmax(const dsa_shape *shape, const int8_t *Qt, const int8_t *Kt,
+                             int32_t *rowmax, void *stream);
+
+const char *dsa_status_string(dsa_status status);
+
+/* Library version, "major.minor". */
+const char *dsa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSA_H */

@@ -1,0 +1,8 @@
+"""MI355X-native Dynamic Sparse Attention forward path (arXiv 2110.11299).
+
+`binding` is the Python face of the C-ABI library built from `csrc/`; `build` compiles it.
+"""
+from . import binding  # noqa: F401
+from .binding import (DSA_BF16, DSA_F32, DsaError, DsaShape, dsa_approx_rowmax, dsa_attention_fwd,  # noqa: F401
+                      dsa_masked_attention, dsa_predict_mask, dsa_sddmm, dsa_sparse_softmax, dsa_spmm,
+                      keep_from_ratio, make_shape, workspace_bytes)

@@ -1,0 +1,208 @@
+"""Thin ctypes binding of libdsa_hip.so: argument marshalling only.
+
+Every function takes torch CUDA tensors (PyTorch owns device memory and streams), passes
+their device pointers and the current stream through the C ABI declared in include/dsa.h
+and returns the output tensors.  There is no fallback: without the built library, or on a
+failed status, these raise.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+_LIB_PATH = Path(__file__).resolve().parent / "libdsa_hip.so"
+_lib = None
+
+DSA_OK = 0
+DSA_F32, DSA_BF16 = 0, 1
+
+EXPORTS = [
+    "dsa_keep_from_ratio", "dsa_workspace_bytes", "dsa_predict_mask", "dsa_sddmm", "dsa_sparse_softmax",
+    "dsa_spmm", "dsa_masked_attention", "dsa_attention_fwd", "dsa_approx_rowmax", "dsa_status_string",
+    "dsa_version",
+]
+
+
+class DsaShape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("L", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("k", ctypes.c_int32), ("keep", ctypes.c_int32), ("vec", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+
+class DsaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib():
+    """The loaded C-ABI library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it first (python -m paper_2110_11299_amd.build "
+                               "or __graft_entry__.build()); there is no fallback path")
+        L = ctypes.CDLL(str(_LIB_PATH))
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        shp = ctypes.POINTER(DsaShape)
+        L.dsa_keep_from_ratio.restype = i32
+        L.dsa_keep_from_ratio.argtypes = [i32, ctypes.c_double]
+        L.dsa_workspace_bytes.restype = sz
+        L.dsa_workspace_bytes.argtypes = [shp]
+        L.dsa_predict_mask.restype = i32
+        L.dsa_predict_mask.argtypes = [shp, vp, vp, vp, vp, sz, vp]
+        L.dsa_sddmm.restype = i32
+        L.dsa_sddmm.argtypes = [shp, vp, vp, vp, vp, vp]
+        L.dsa_sparse_softmax.restype = i32
+        L.dsa_sparse_softmax.argtypes = [shp, vp, vp, vp]
+        L.dsa_spmm.restype = i32
+        L.dsa_spmm.argtypes = [shp, vp, vp, vp, vp, vp]
+        L.dsa_masked_attention.restype = i32
+        L.dsa_masked_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp]
+        L.dsa_attention_fwd.restype = i32
+        L.dsa_attention_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.dsa_approx_rowmax.restype = i32
+        L.dsa_approx_rowmax.argtypes = [shp, vp, vp, vp, vp]
+        L.dsa_status_string.restype = ctypes.c_char_p
+        L.dsa_status_string.argtypes = [i32]
+        L.dsa_version.restype = ctypes.c_char_p
+        L.dsa_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().dsa_status_string(status).decode()
+
+
+def version() -> str:
+    return lib().dsa_version().decode()
+
+
+def keep_from_ratio(L: int, ratio: float) -> int:
+    return int(lib().dsa_keep_from_ratio(L, ratio))
+
+
+def make_shape(B, H, L, d, k, keep, vec, dtype, scale) -> DsaShape:
+    return DsaShape(B, H, L, d, k, keep, vec, dtype, scale)
+
+
+def workspace_bytes(shape: DsaShape) -> int:
+    return int(lib().dsa_workspace_bytes(ctypes.byref(shape)))
+
+
+def _check(status: int, where: str):
+    if status != DSA_OK:
+        raise DsaError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, shape):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype
+            and tuple(t.shape) == tuple(shape)):
+        raise ValueError(f"expected a contiguous CUDA tensor {dtype} {tuple(shape)}, got "
+                         f"{getattr(t, 'dtype', type(t))} {tuple(getattr(t, 'shape', ()))}")
+    return t
+
+
+def _qkv_dtype(shape: DsaShape):
+    import torch
+    return torch.float32 if shape.dtype == DSA_F32 else torch.bfloat16
+
+
+def _dims(s: DsaShape):
+    return (s.B, s.H, s.L, s.d), (s.B, s.H, s.L, s.k), (s.B, s.H, s.L // s.vec, s.keep), (s.B, s.H, s.L, s.keep)
+
+
+def alloc_workspace(shape: DsaShape, device="cuda"):
+    import torch
+    n = workspace_bytes(shape)
+    return torch.empty(max(n, 16), dtype=torch.uint8, device=device)
+
+
+def dsa_predict_mask(shape, Qt, Kt, idx=None, ws=None):
+    import torch
+    _, tk, ti, _ = _dims(shape)
+    _dev(Qt, torch.int8, tk); _dev(Kt, torch.int8, tk)
+    idx = torch.empty(ti, dtype=torch.int32, device=Qt.device) if idx is None else _dev(idx, torch.int32, ti)
+    ws = alloc_workspace(shape, Qt.device) if ws is None else ws
+    _check(lib().dsa_predict_mask(ctypes.byref(shape), _ptr(Qt), _ptr(Kt), _ptr(idx), _ptr(ws),
+                                  ws.numel(), _stream()), "dsa_predict_mask")
+    return idx
+
+
+def dsa_sddmm(shape, Q, K, idx, S=None):
+    import torch
+    tq, _, ti, ts = _dims(shape)
+    dt = _qkv_dtype(shape)
+    _dev(Q, dt, tq); _dev(K, dt, tq); _dev(idx, torch.int32, ti)
+    S = torch.empty(ts, dtype=torch.float32, device=Q.device) if S is None else _dev(S, torch.float32, ts)
+    _check(lib().dsa_sddmm(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(idx), _ptr(S), _stream()), "dsa_sddmm")
+    return S
+
+
+def dsa_sparse_softmax(shape, S, P=None):
+    import torch
+    _, _, _, ts = _dims(shape)
+    _dev(S, torch.float32, ts)
+    P = torch.empty_like(S) if P is None else _dev(P, torch.float32, ts)
+    _check(lib().dsa_sparse_softmax(ctypes.byref(shape), _ptr(S), _ptr(P), _stream()), "dsa_sparse_softmax")
+    return P
+
+
+def dsa_spmm(shape, P, idx, V, O=None):
+    import torch
+    tq, _, ti, ts = _dims(shape)
+    _dev(P, torch.float32, ts); _dev(idx, torch.int32, ti); _dev(V, _qkv_dtype(shape), tq)
+    O = torch.empty(tq, dtype=torch.float32, device=V.device) if O is None else _dev(O, torch.float32, tq)
+    _check(lib().dsa_spmm(ctypes.byref(shape), _ptr(P), _ptr(idx), _ptr(V), _ptr(O), _stream()), "dsa_spmm")
+    return O
+
+
+def dsa_masked_attention(shape, Q, K, V, idx, O=None):
+    import torch
+    tq, _, ti, _ = _dims(shape)
+    dt = _qkv_dtype(shape)
+    _dev(Q, dt, tq); _dev(K, dt, tq); _dev(V, dt, tq); _dev(idx, torch.int32, ti)
+    O = torch.empty(tq, dtype=torch.float32, device=Q.device) if O is None else _dev(O, torch.float32, tq)
+    _check(lib().dsa_masked_attention(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(O),
+                                      _stream()), "dsa_masked_attention")
+    return O
+
+
+def dsa_attention_fwd(shape, Q, K, V, Qt, Kt, O=None, idx_out=None, ws=None, want_idx=True):
+    """Returns (O, idx); idx is None when want_idx is False and no idx_out was given."""
+    import torch
+    tq, tk, ti, _ = _dims(shape)
+    dt = _qkv_dtype(shape)
+    _dev(Q, dt, tq); _dev(K, dt, tq); _dev(V, dt, tq); _dev(Qt, torch.int8, tk); _dev(Kt, torch.int8, tk)
+    O = torch.empty(tq, dtype=torch.float32, device=Q.device) if O is None else _dev(O, torch.float32, tq)
+    if idx_out is None and want_idx:
+        idx_out = torch.empty(ti, dtype=torch.int32, device=Q.device)
+    elif idx_out is not None:
+        _dev(idx_out, torch.int32, ti)
+    ws = alloc_workspace(shape, Q.device) if ws is None else ws
+    _check(lib().dsa_attention_fwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Qt), _ptr(Kt),
+                                   _ptr(O), _ptr(idx_out), _ptr(ws), ws.numel(), _stream()),
+           "dsa_attention_fwd")
+    return O, idx_out
+
+
+def dsa_approx_rowmax(shape, Qt, Kt, rowmax=None):
+    import torch
+    _, tk, _, _ = _dims(shape)
+    _dev(Qt, torch.int8, tk); _dev(Kt, torch.int8, tk)
+    tr = (shape.B, shape.H, shape.L)
+    rowmax = torch.empty(tr, dtype=torch.int32, device=Qt.device) if rowmax is None else _dev(rowmax, torch.int32, tr)
+    _check(lib().dsa_approx_rowmax(ctypes.byref(shape), _ptr(Qt), _ptr(Kt), _ptr(rowmax), _stream()),
+           "dsa_approx_rowmax")
+    return rowmax

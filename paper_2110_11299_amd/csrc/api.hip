@@ -1,0 +1,169 @@
+// C ABI of libdsa_hip.so: argument checking on the host, then dispatch to the launchers.
+// Nothing here touches the device before every check has passed.
+#include "dsa_internal.h"
+
+#include <math.h>
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Checks that do not depend on which entry point is called.
+dsa_status check_common(const dsa_shape *sh)
+{
+    if (!sh) return DSA_ERR_NULL;
+    if (sh->B < 1 || sh->H < 1 || sh->L < 1) return DSA_ERR_SHAPE;
+    if ((int64_t)sh->B * sh->H > (1 << 24)) return DSA_ERR_SHAPE;
+    if (sh->vec != 1 && sh->vec != 8) return DSA_ERR_UNSUPPORTED;
+    if (sh->L % sh->vec) return DSA_ERR_SHAPE;
+    if (sh->keep < 1 || sh->keep > sh->L) return DSA_ERR_SHAPE;
+    if ((int64_t)sh->B * sh->H * sh->L > (int64_t)1 << 31) return DSA_ERR_UNSUPPORTED;
+    return DSA_OK;
+}
+
+dsa_status check_predict(const dsa_shape *sh)
+{
+    if (dsa_status s = check_common(sh)) return s;
+    if (sh->k < 16 || sh->k > 128 || sh->k % 16) return DSA_ERR_UNSUPPORTED;
+    if (sh->L > dsa::predict_max_L()) return DSA_ERR_UNSUPPORTED;
+    return DSA_OK;
+}
+
+dsa_status check_attention(const dsa_shape *sh)
+{
+    if (dsa_status s = check_common(sh)) return s;
+    if (sh->d != 64 && sh->d != 128) return DSA_ERR_UNSUPPORTED;
+    if (sh->dtype != DSA_F32 && sh->dtype != DSA_BF16) return DSA_ERR_UNSUPPORTED;
+    if (sh->keep > dsa::attention_max_keep()) return DSA_ERR_UNSUPPORTED;
+    if (!isfinite(sh->scale)) return DSA_ERR_SHAPE;
+    return DSA_OK;
+}
+
+size_t idx_bytes(const dsa_shape &sh)
+{
+    return (size_t)sh.B * sh.H * (sh.L / sh.vec) * sh.keep * sizeof(int32_t);
+}
+
+size_t round_up_256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+dsa_status from_hip(hipError_t e) { return e == hipSuccess ? DSA_OK : DSA_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+int32_t dsa_keep_from_ratio(int32_t L, double ratio)
+{
+    if (L < 1) return 0;
+    double x = floor(ratio * (double)L + 0.5);
+    if (!(x >= 1.0)) x = 1.0;
+    if (x > (double)L) x = (double)L;
+    return (int32_t)x;
+}
+
+size_t dsa_workspace_bytes(const dsa_shape *sh)
+{
+    if (check_predict(sh) != DSA_OK) return 0;
+    // [mask for dsa_attention_fwd when the caller does not want it back][predict scratch]
+    return round_up_256(idx_bytes(*sh)) + round_up_256(dsa::predict_workspace_bytes(*sh));
+}
+
+dsa_status dsa_predict_mask(const dsa_shape *sh, const int8_t *Qt, const int8_t *Kt, int32_t *idx,
+                            void *ws, size_t ws_bytes, void *stream)
+{
+    if (!sh || !Qt || !Kt || !idx) return DSA_ERR_NULL;
+    if (dsa_status s = check_predict(sh)) return s;
+    if (!aligned16(Qt) || !aligned16(Kt) || !aligned16(idx) || !aligned16(ws)) return DSA_ERR_ALIGN;
+    const size_t need = round_up_256(dsa::predict_workspace_bytes(*sh));
+    if (need && (!ws || ws_bytes < need)) return DSA_ERR_WORKSPACE;
+    return from_hip(dsa::launch_predict(*sh, Qt, Kt, idx, ws, (hipStream_t)stream));
+}
+
+dsa_status dsa_sddmm(const dsa_shape *sh, const void *Q, const void *K, const int32_t *idx, float *S,
+                     void *stream)
+{
+    if (!sh || !Q || !K || !idx || !S) return DSA_ERR_NULL;
+    if (dsa_status s = check_attention(sh)) return s;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(idx) || !aligned16(S)) return DSA_ERR_ALIGN;
+    return from_hip(dsa::launch_attention(dsa::kSddmm, *sh, Q, K, nullptr, idx, nullptr, S, nullptr,
+                                          (hipStream_t)stream));
+}
+
+dsa_status dsa_sparse_softmax(const dsa_shape *sh, const float *S, float *P, void *stream)
+{
+    if (!sh || !S || !P) return DSA_ERR_NULL;
+    if (dsa_status s = check_common(sh)) return s;
+    if (!aligned16(S) || !aligned16(P)) return DSA_ERR_ALIGN;
+    return from_hip(dsa::launch_softmax(*sh, S, P, (hipStream_t)stream));
+}
+
+dsa_status dsa_spmm(const dsa_shape *sh, const float *P, const int32_t *idx, const void *V, float *O,
+                    void *stream)
+{
+    if (!sh || !P || !idx || !V || !O) return DSA_ERR_NULL;
+    if (dsa_status s = check_attention(sh)) return s;
+    if (!aligned16(P) || !aligned16(idx) || !aligned16(V) || !aligned16(O)) return DSA_ERR_ALIGN;
+    return from_hip(dsa::launch_attention(dsa::kSpmm, *sh, nullptr, nullptr, V, idx, P, nullptr, O,
+                                          (hipStream_t)stream));
+}
+
+dsa_status dsa_masked_attention(const dsa_shape *sh, const void *Q, const void *K, const void *V,
+                                const int32_t *idx, float *O, void *stream)
+{
+    if (!sh || !Q || !K || !V || !idx || !O) return DSA_ERR_NULL;
+    if (dsa_status s = check_attention(sh)) return s;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(idx) || !aligned16(O))
+        return DSA_ERR_ALIGN;
+    return from_hip(dsa::launch_attention(dsa::kFused, *sh, Q, K, V, idx, nullptr, nullptr, O,
+                                          (hipStream_t)stream));
+}
+
+dsa_status dsa_attention_fwd(const dsa_shape *sh, const void *Q, const void *K, const void *V,
+                             const int8_t *Qt, const int8_t *Kt, float *O, int32_t *idx_out, void *ws,
+                             size_t ws_bytes, void *stream)
+{
+    if (!sh || !Q || !K || !V || !Qt || !Kt || !O) return DSA_ERR_NULL;
+    if (dsa_status s = check_predict(sh)) return s;
+    if (dsa_status s = check_attention(sh)) return s;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(Qt) || !aligned16(Kt) ||
+        !aligned16(O) || !aligned16(idx_out) || !aligned16(ws))
+        return DSA_ERR_ALIGN;
+    const size_t mask_bytes = round_up_256(idx_bytes(*sh));
+    const size_t scratch = round_up_256(dsa::predict_workspace_bytes(*sh));
+    const size_t need = (idx_out ? 0 : mask_bytes) + scratch;
+    if (need && (!ws || ws_bytes < need)) return DSA_ERR_WORKSPACE;
+    int32_t *idx = idx_out ? idx_out : static_cast<int32_t *>(ws);
+    void *pws = idx_out ? ws : static_cast<void *>(static_cast<char *>(ws) + mask_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    if (hipError_t e = dsa::launch_predict(*sh, Qt, Kt, idx, pws, st)) return from_hip(e);
+    return from_hip(dsa::launch_attention(dsa::kFused, *sh, Q, K, V, idx, nullptr, nullptr, O, st));
+}
+
+dsa_status dsa_approx_rowmax(const dsa_shape *sh, const int8_t *Qt, const int8_t *Kt, int32_t *rowmax,
+                             void *stream)
+{
+    if (!sh || !Qt || !Kt || !rowmax) return DSA_ERR_NULL;
+    if (sh->B < 1 || sh->H < 1 || sh->L < 1) return DSA_ERR_SHAPE;
+    if ((int64_t)sh->B * sh->H * sh->L > (int64_t)1 << 31) return DSA_ERR_UNSUPPORTED;
+    if (sh->k < 16 || sh->k > 128 || sh->k % 16) return DSA_ERR_UNSUPPORTED;
+    if (!aligned16(Qt) || !aligned16(Kt) || !aligned16(rowmax)) return DSA_ERR_ALIGN;
+    return from_hip(dsa::launch_rowmax(*sh, Qt, Kt, rowmax, (hipStream_t)stream));
+}
+
+const char *dsa_status_string(dsa_status s)
+{
+    switch (s) {
+    case DSA_OK: return "ok";
+    case DSA_ERR_NULL: return "null pointer";
+    case DSA_ERR_SHAPE: return "dimension out of range";
+    case DSA_ERR_UNSUPPORTED: return "unsupported configuration";
+    case DSA_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case DSA_ERR_WORKSPACE: return "workspace missing or too small";
+    case DSA_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+const char *dsa_version(void) { return "0.1"; }
+
+}  // extern "C"

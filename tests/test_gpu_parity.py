@@ -1,0 +1,195 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Mask and index lists bit-exact; float outputs within max-abs 1e-4 (fp32
+inputs) / 2e-2 (bf16 inputs)."""
+import numpy as np
+import pytest
+
+import dsa_inputs as di
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def dsa():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need the MI355X: run them with -m gpu on the GPU box")
+    import paper_2110_11299_amd as pkg
+    pkg.binding.lib()          # raises if the HIP library was not built: no fallback
+    return pkg
+
+
+def to_dev(x: di.DsaInputs):
+    import torch
+    out = {}
+    for name in ("Q", "K", "V"):
+        a = x.storage(name)
+        if x.cfg.dtype == "bf16":
+            out[name] = torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        else:
+            out[name] = torch.from_numpy(a).cuda()
+    out["Qt"] = torch.from_numpy(x.Qt).cuda()
+    out["Kt"] = torch.from_numpy(x.Kt).cuda()
+    return out
+
+
+def shape_of(pkg, cfg, keep=None):
+    return pkg.make_shape(cfg.B, cfg.H, cfg.L, cfg.d, cfg.k, cfg.keep if keep is None else keep, cfg.vec,
+                          pkg.DSA_F32 if cfg.dtype == "f32" else pkg.DSA_BF16, float(cfg.scale))
+
+
+def check_path(pkg, oracle, x, *, staged=True, label=""):
+    """Runs every entry point on x and compares with the oracle.  Returns max-abs errors."""
+    import torch
+    cfg = x.cfg
+    sh = shape_of(pkg, cfg)
+    dev = to_dev(x)
+    tol = TOL[cfg.dtype]
+    print(f"[{label or cfg.name}] B={cfg.B} H={cfg.H} L={cfg.L} d={cfg.d} k={cfg.k} vec={cfg.vec} "
+          f"keep={cfg.keep} {cfg.dtype}", flush=True)
+
+    want_idx = oracle.predict_mask(x.Qt, x.Kt, cfg.keep, cfg.vec)
+    want_O, want_S, want_P = oracle.masked_attention(x.Q, x.K, x.V, want_idx, cfg.scale, cfg.vec,
+                                                     return_sp=True)
+
+    # (a)+(b)
+    idx = pkg.dsa_predict_mask(sh, dev["Qt"], dev["Kt"])
+    torch.cuda.synchronize()
+    got_idx = idx.cpu().numpy().reshape(-1, cfg.keep)
+    mism = int((got_idx != want_idx).any(axis=1).sum())
+    assert mism == 0, f"{mism} of {want_idx.shape[0]} units differ in the mask"
+
+    errs = {}
+    if staged:
+        S = pkg.dsa_sddmm(sh, dev["Q"], dev["K"], idx)
+        P = pkg.dsa_sparse_softmax(sh, S)
+        O = pkg.dsa_spmm(sh, P, idx, dev["V"])
+        torch.cuda.synchronize()
+        errs["S"] = float(np.abs(S.cpu().numpy().reshape(want_S.shape) - want_S).max())
+        errs["P"] = float(np.abs(P.cpu().numpy().reshape(want_P.shape) - want_P).max())
+        errs["O_staged"] = float(np.abs(O.cpu().numpy().reshape(want_O.shape) - want_O).max())
+        rows = P.sum(dim=-1)
+        assert float((rows - 1).abs().max()) < 1e-5 and float(P.min()) >= 0
+        # in-place softmax gives the same bits
+        P2 = pkg.dsa_sparse_softmax(sh, S, S)
+        assert torch.equal(P2, P)
+    O = pkg.dsa_masked_attention(sh, dev["Q"], dev["K"], dev["V"], idx)
+    torch.cuda.synchronize()
+    errs["O_masked"] = float(np.abs(O.cpu().numpy().reshape(want_O.shape) - want_O).max())
+
+    O2, idx2 = pkg.dsa_attention_fwd(sh, dev["Q"], dev["K"], dev["V"], dev["Qt"], dev["Kt"])
+    O3, none = pkg.dsa_attention_fwd(sh, dev["Q"], dev["K"], dev["V"], dev["Qt"], dev["Kt"], want_idx=False)
+    torch.cuda.synchronize()
+    assert none is None
+    assert torch.equal(idx2, idx), "fused entry point returned a different mask"
+    assert torch.equal(O2, O) and torch.equal(O3, O), "fused entry point is not reproducible"
+    errs["O_fwd"] = float(np.abs(O2.cpu().numpy().reshape(want_O.shape) - want_O).max())
+    print(f"    max-abs errors: {errs}", flush=True)
+    for name, e in errs.items():
+        assert e <= tol, f"{name}: max-abs error {e} > {tol}"
+    return errs
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4f", "C4v", "C5"])
+def test_config_parity(dsa, oracle, workload, name):
+    check_path(dsa, oracle, workload(name), staged=True)
+
+
+EDGE = [
+    # ragged lengths (not a multiple of the wavefront or of any tile), odd head counts
+    dict(B=1, H=3, L=100, d=64, dtype="f32", k=16, vec=1, keep=7),
+    dict(B=3, H=1, L=104, d=64, dtype="bf16", k=32, vec=8, keep=13),
+    dict(B=1, H=2, L=1000, d=128, dtype="f32", k=48, vec=1, keep=100),
+    dict(B=1, H=2, L=1096, d=128, dtype="bf16", k=128, vec=8, keep=55),
+    dict(B=2, H=2, L=777, d=64, dtype="bf16", k=64, vec=1, keep=39),
+    # degenerate keeps
+    dict(B=1, H=2, L=96, d=64, dtype="f32", k=16, vec=1, keep=1),
+    dict(B=1, H=2, L=96, d=64, dtype="f32", k=16, vec=8, keep=96),
+    dict(B=1, H=1, L=8, d=64, dtype="bf16", k=16, vec=8, keep=8),
+    dict(B=1, H=1, L=1, d=64, dtype="f32", k=16, vec=1, keep=1),
+    dict(B=1, H=1, L=520, d=64, dtype="f32", k=32, vec=1, keep=519),
+    dict(B=1, H=1, L=2304, d=64, dtype="bf16", k=32, vec=1, keep=1200, n_global=5),
+]
+
+
+@pytest.mark.parametrize("spec", EDGE, ids=lambda s: "-".join(f"{k}{v}" for k, v in s.items()))
+def test_edge_shapes(dsa, oracle, spec):
+    cfg = di.custom_config(rank=4, seed=31 + spec["L"], **spec)
+    check_path(dsa, oracle, di.make_inputs(cfg), staged=True, label="edge")
+
+
+@pytest.mark.parametrize("vec", [1, 8])
+@pytest.mark.parametrize("lo,hi", [(0, 0), (-1, 1), (-3, 3), (-127, 127)])
+def test_mask_with_heavy_ties(dsa, oracle, vec, lo, hi):
+    """Narrow int8 ranges make most scores collide, so the lowest-index rule decides
+    almost every list; all-zero projections make it decide everything."""
+    import torch
+    B, H, L, k = 2, 3, 1536, 32
+    Qt, Kt = di.random_int8_case(5 + hi, B, H, L, k, lo=lo, hi=hi)
+    for keep in (1, 77, 500):
+        sh = dsa.make_shape(B, H, L, 64, k, keep, vec, dsa.DSA_F32, 0.125)
+        print(f"[ties] range=({lo},{hi}) vec={vec} keep={keep}", flush=True)
+        idx = dsa.dsa_predict_mask(sh, torch.from_numpy(Qt).cuda(), torch.from_numpy(Kt).cuda())
+        want = oracle.predict_mask(Qt, Kt, keep, vec)
+        assert np.array_equal(idx.cpu().numpy().reshape(want.shape), want)
+
+
+def test_outputs_stay_inside_their_buffers(dsa, oracle, workload):
+    """Guard words around idx and O must survive."""
+    import torch
+    x = workload("C1")
+    cfg, dev = x.cfg, to_dev(x)
+    sh = shape_of(dsa, cfg)
+    pad = 64
+    n_idx, n_o = cfg.units * cfg.keep, cfg.N * cfg.L * cfg.d
+    idx_buf = torch.full((n_idx + 2 * pad,), -7, dtype=torch.int32, device="cuda")
+    o_buf = torch.full((n_o + 2 * pad,), 123.0, dtype=torch.float32, device="cuda")
+    idx = idx_buf[pad:pad + n_idx].view(cfg.B, cfg.H, cfg.L // cfg.vec, cfg.keep)
+    O = o_buf[pad:pad + n_o].view(cfg.B, cfg.H, cfg.L, cfg.d)
+    dsa.dsa_attention_fwd(sh, dev["Q"], dev["K"], dev["V"], dev["Qt"], dev["Kt"], O=O, idx_out=idx)
+    torch.cuda.synchronize()
+    assert bool((idx_buf[:pad] == -7).all()) and bool((idx_buf[pad + n_idx:] == -7).all())
+    assert bool((o_buf[:pad] == 123.0).all()) and bool((o_buf[pad + n_o:] == 123.0).all())
+    assert bool((idx >= 0).all()) and bool((idx < cfg.L).all())
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C4f", "C5"])
+def test_rowmax_of_approximate_scores(dsa, oracle, workload, name):
+    """The int8 matrix-core contraction alone: row maxima of S~ are exact integers."""
+    import torch
+    x = workload(name)
+    cfg = x.cfg
+    sh = shape_of(dsa, cfg)
+    print(f"[rowmax] {name}", flush=True)
+    got = dsa.dsa_approx_rowmax(sh, torch.from_numpy(x.Qt).cuda(), torch.from_numpy(x.Kt).cuda())
+    torch.cuda.synchronize()
+    got = got.cpu().numpy().reshape(-1)
+    rng = np.random.default_rng(0)
+    rows = np.unique(np.concatenate([[0, cfg.N * cfg.L - 1], rng.integers(0, cfg.N * cfg.L, 512)]))
+    want = oracle.approx_scores(x.Qt, x.Kt, vec=1, units=rows).max(axis=1)
+    assert np.array_equal(got[rows], want)
+
+
+def test_rowmax_ragged(dsa, oracle):
+    import torch
+    for (L, k) in [(1, 16), (33, 16), (100, 48), (257, 128)]:
+        Qt, Kt = di.random_int8_case(L, 1, 3, L, k)
+        sh = dsa.make_shape(1, 3, L, 64, k, 1, 1, dsa.DSA_F32, 1.0)
+        got = dsa.dsa_approx_rowmax(sh, torch.from_numpy(Qt).cuda(), torch.from_numpy(Kt).cuda())
+        want = oracle.approx_scores(Qt, Kt).max(axis=1)
+        assert np.array_equal(got.cpu().numpy().reshape(-1), want), (L, k)
+
+
+def test_errors_launch_nothing(dsa):
+    import torch
+    sh = dsa.make_shape(1, 1, 64, 64, 16, 65, 1, dsa.DSA_F32, 0.125)      # keep > L
+    Qt = torch.zeros((1, 1, 64, 16), dtype=torch.int8, device="cuda")
+    with pytest.raises(dsa.DsaError) as e:
+        dsa.dsa_predict_mask(sh, Qt, Qt)
+    assert e.value.status == 2
+    sh = dsa.make_shape(1, 1, 64, 64, 16, 8, 4, dsa.DSA_F32, 0.125)       # vec = 4
+    with pytest.raises(dsa.DsaError) as e:
+        dsa.dsa_predict_mask(sh, Qt, Qt)
+    assert e.value.status == 3
