@@ -42,6 +42,10 @@ def lib():
         if not _LIB_PATH.exists():
             raise RuntimeError(f"{_LIB_PATH} is missing: build it first (python -m paper_2110_11299_amd.build "
                                "or __graft_entry__.build()); there is no fallback path")
+        # PyTorch ships its own HIP runtime under the same soname as the system one.  Import it
+        # first, so that this library binds to the runtime that owns torch's streams and memory
+        # instead of pulling a second runtime into the process.
+        import torch  # noqa: F401
         L = ctypes.CDLL(str(_LIB_PATH))
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
         shp = ctypes.POINTER(DsaShape)
