@@ -4,6 +4,8 @@
 // the selection is exact: larger score first, lower key index among equals, list ascending.
 #include "dsa_internal.h"
 
+#include <stdlib.h>
+
 namespace dsa {
 namespace {
 
@@ -13,23 +15,41 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int kUnitThreads = 256;
 constexpr int kUnitMaxL = 32768;     // one unit's scores in LDS: 128 KB
 
+// Wavefront reductions without LDS traffic: butterfly inside each row of 16 lanes with DPP
+// (quad permutes, then the two mirrors), then the four row results through v_readlane into
+// scalar registers.  The result is wavefront-uniform and lives in an SGPR.
+template <int CTRL> __device__ __forceinline__ int dpp_move(int x)
+{
+    return __builtin_amdgcn_update_dpp(x, x, CTRL, 0xF, 0xF, false);
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+
 __device__ __forceinline__ int wave_sum(int x)
 {
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) x += __shfl_xor(x, off, kWave);
-    return x;
+    x += dpp_move<kDppXor1>(x);
+    x += dpp_move<kDppXor2>(x);
+    x += dpp_move<kDppHalfMirror>(x);
+    x += dpp_move<kDppMirror>(x);
+    return __builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16) +
+           __builtin_amdgcn_readlane(x, 32) + __builtin_amdgcn_readlane(x, 48);
 }
 __device__ __forceinline__ int wave_max(int x)
 {
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) x = max(x, __shfl_xor(x, off, kWave));
-    return x;
+    x = max(x, dpp_move<kDppXor1>(x));
+    x = max(x, dpp_move<kDppXor2>(x));
+    x = max(x, dpp_move<kDppHalfMirror>(x));
+    x = max(x, dpp_move<kDppMirror>(x));
+    return max(max(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
+               max(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
 }
 __device__ __forceinline__ int wave_min(int x)
 {
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) x = min(x, __shfl_xor(x, off, kWave));
-    return x;
+    x = min(x, dpp_move<kDppXor1>(x));
+    x = min(x, dpp_move<kDppXor2>(x));
+    x = min(x, dpp_move<kDppHalfMirror>(x));
+    x = min(x, dpp_move<kDppMirror>(x));
+    return min(min(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
+               min(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
 }
 
 // One workgroup per selection unit.  All L scores of the unit are computed with packed int8
@@ -122,6 +142,569 @@ __global__ __launch_bounds__(kUnitThreads) void predict_unit(const int8_t *__res
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Tiled predictor.  One workgroup of W wavefronts owns 16 selection units of one head and sweeps
+// the keys in chunks of 16*W*TC.  Matrix-core orientation: keys are the rows (A operand), units
+// the columns (B operand) of v_mfma_i32_16x16x{32,64}_i8, so lane (c = lane%16, g = lane/16)
+// ends up holding, for unit c, the scores of 4 keys per tile.  The 4*W "holders" (wave, g) of a
+// unit each own 4*TC consecutive keys of the chunk, which makes every lane's score stream
+// contiguous in key order.  For vec = 8 the unit's 8 query rows are simply concatenated along
+// the contraction (length 8k, the key operand repeating with period k): the matrix core
+// produces the group sum itself.
+//
+// Selection never sorts and never re-reads a score from memory.  Scores stay in registers.
+//  (A) each lane keeps NB bucket maxima of its stream;
+//  (B) the keep-th largest of a unit's bucket maxima is a lower bound T0 of its keep-th largest
+//      score (the buckets are disjoint, so that many distinct scores reach T0);
+//  (C) each lane compares its scores with T0: the outcomes, shifted into 32-bit words, ARE the
+//      unit's bitmap over keys, and the scores that pass are appended to the lane's own small
+//      LDS segment (every score is written at the current end of the segment, and the end only
+//      moves past it if it passed) -- 5 VALU operations and one LDS write per score, no branch;
+//  (D) one wavefront per unit walks the bitmap in key order, pairs each candidate key with its
+//      score from the segments, bisects for the exact threshold in registers and writes the kept
+//      keys in ascending order, breaking ties by key index through ballot prefix counts.
+// A unit whose candidates do not fit (massive ties, very large keep) takes a slower path that
+// recomputes scores from Q~, K~ with packed dot products.
+// ---------------------------------------------------------------------------------------------
+constexpr int kTileUnits = 16;
+
+// Optional per-phase cycle accounting for tuning; compiled out of the library.
+#ifdef DSA_PHASE_TIMING
+__device__ unsigned long long g_phase_cycles[16];
+#define PHASE_MARK(slot)                                    \
+    do {                                                    \
+        const long long now_ = clock64();                   \
+        ph_[slot] += (unsigned long long)(now_ - t_phase_); \
+        t_phase_ = now_;                                    \
+    } while (0)
+#define PHASE_START()                                              \
+    unsigned long long ph_[16];                                    \
+    _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) ph_[i_] = 0; \
+    long long t_phase_ = clock64()
+#define PHASE_COUNT(slot, v) do { ph_[slot] += (unsigned long long)(v); } while (0)
+#define PHASE_FLUSH()                                                                                  \
+    do {                                                                                               \
+        if (lane == 0) {                                                                               \
+            _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) atomicAdd(&g_phase_cycles[i_], ph_[i_]); \
+        }                                                                                              \
+    } while (0)
+#else
+#define PHASE_MARK(slot) do { } while (0)
+#define PHASE_START() do { } while (0)
+#define PHASE_COUNT(slot, v) do { } while (0)
+#define PHASE_FLUSH() do { } while (0)
+#endif
+// Tuning aid: a build with -DDSA_PREDICT_STOP=n leaves the kernel after phase n (1 = A .. 3 = C); the
+// output is then meaningless.  Never defined for the library.
+#ifndef DSA_PREDICT_STOP
+#define DSA_PREDICT_STOP 0
+#endif
+
+constexpr int kCompactCap = 512;      // candidates of one unit that the register path handles
+constexpr int kSegSlots = 1024;       // segment slots per unit (all holders, all chunks)
+constexpr size_t kLdsBudget = 150 * 1024;       // of the 160 KB a gfx950 workgroup may use
+constexpr int kAllCandidates = INT32_MIN + 1;   // T0 when no bound is known; padding scores are INT32_MIN
+
+template <int KSTEP> struct Mfma;
+template <> struct Mfma<32> {
+    typedef long op_t;
+    static constexpr int kBytes = 8;
+    static __device__ __forceinline__ op_t load(const int8_t *p) { return *reinterpret_cast<const long *>(p); }
+    static __device__ __forceinline__ op_t zero() { return 0; }
+    static __device__ __forceinline__ v4i run(op_t a, op_t b, v4i c)
+    {
+        return __builtin_amdgcn_mfma_i32_16x16x32_i8(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Mfma<64> {
+    typedef v4i op_t;
+    static constexpr int kBytes = 16;
+    static __device__ __forceinline__ op_t load(const int8_t *p) { return *reinterpret_cast<const v4i *>(p); }
+    static __device__ __forceinline__ op_t zero() { return v4i{0, 0, 0, 0}; }
+    static __device__ __forceinline__ v4i run(op_t a, op_t b, v4i c)
+    {
+        return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+    }
+};
+
+// Inclusive prefix sum over the 64 lanes: Hillis-Steele inside each row of 16 lanes with DPP row
+// shifts (zero fill), then the totals of the lower rows through v_readlane.  *total = wavefront sum.
+__device__ __forceinline__ int wave_incl_scan(int x, int lane, int *total)
+{
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, true);   // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, true);   // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, true);   // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, true);   // row_shr:8
+    const int t0 = __builtin_amdgcn_readlane(x, 15), t1 = __builtin_amdgcn_readlane(x, 31),
+              t2 = __builtin_amdgcn_readlane(x, 47), t3 = __builtin_amdgcn_readlane(x, 63);
+    const int row = lane >> 4;
+    x += (row >= 1 ? t0 : 0) + (row >= 2 ? t1 : 0) + (row >= 3 ? t2 : 0);
+    *total = t0 + t1 + t2 + t3;
+    return x;
+}
+
+// Makes LDS writes of some lanes of a wavefront visible to reads of its other lanes.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Exact score of (unit, key): sum over the unit's vec rows of the int8 dot product.
+__device__ __forceinline__ int unit_key_score(const int *__restrict__ qu, const int8_t *__restrict__ krow,
+                                              int vec, int k4)
+{
+    int s = 0;
+    for (int c4 = 0; c4 < k4; c4 += 4) {
+        const v4i kk = *reinterpret_cast<const v4i *>(krow + 4 * c4);
+        for (int r = 0; r < vec; ++r) {
+            const int *q = qu + r * k4 + c4;
+            s = __builtin_amdgcn_sdot4(q[0], kk.x, s, false);
+            s = __builtin_amdgcn_sdot4(q[1], kk.y, s, false);
+            s = __builtin_amdgcn_sdot4(q[2], kk.z, s, false);
+            s = __builtin_amdgcn_sdot4(q[3], kk.w, s, false);
+        }
+    }
+    return s;
+}
+
+// The keep-th largest of the values a wavefront holds in registers (NR per lane, unused slots
+// INT32_MIN): the largest T with count(v >= T) >= keep, by bisection on the value.  lo and hi are
+// wavefront-uniform; needs count(v >= lo) >= keep and hi >= every value.  Every probe is above
+// INT32_MIN, so unused slots never count.
+template <int NR>
+__device__ __forceinline__ int kth_largest(const int (&v)[NR], int keep, int lo, int hi)
+{
+    lo = __builtin_amdgcn_readfirstlane(lo);
+    hi = __builtin_amdgcn_readfirstlane(hi);
+    while (lo < hi) {
+        const int mid = (int)(lo + ((long long)hi - lo + 1) / 2);
+        int cnt = 0;
+#pragma unroll
+        for (int i = 0; i < NR; ++i) cnt += __popcll(__ballot(v[i] >= mid));
+        if (cnt >= keep) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// (A) for one wavefront and one chunk: scores of TC tiles into registers plus bucket maxima.
+// Key rows are loaded unconditionally from clamped addresses: a key beyond L only feeds output
+// rows that TAIL overwrites with INT32_MIN, and a contraction piece beyond Ka meets a zero unit
+// operand, so neither needs a zeroed key operand.
+template <int TC, int NB, int KSTEP, int MAXSTEPS, bool TAIL>
+__device__ __forceinline__ void score_chunk(v4i (&acc)[TC], int (&bmax)[NB], const int8_t *__restrict__ Kh,
+                                            int k, int L, int op_lo, int out_lo, int nsteps, bool same_kop,
+                                            const typename Mfma<KSTEP>::op_t (&qop)[MAXSTEPS],
+                                            const int (&koff)[MAXSTEPS])
+{
+    typedef Mfma<KSTEP> M;
+    constexpr int BATCH = 8;
+#pragma unroll
+    for (int t0 = 0; t0 < TC; t0 += BATCH) {
+        typename M::op_t kop[BATCH];
+        const int8_t *krow[BATCH];
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+            int key = op_lo + 4 * (t0 + b);
+            if (TAIL) key = min(key, L - 1);
+            krow[b] = Kh + (size_t)key * k;
+            kop[b] = M::load(krow[b] + koff[0]);
+        }
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+            const int t = t0 + b;
+            v4i a = {0, 0, 0, 0};
+            a = M::run(kop[b], qop[0], a);
+#pragma unroll
+            for (int s = 1; s < MAXSTEPS; ++s) {
+                if (s < nsteps) {
+                    if (!same_kop) kop[b] = M::load(krow[b] + koff[s]);
+                    a = M::run(kop[b], qop[s], a);
+                }
+            }
+            if (TAIL) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (out_lo + 4 * t + i >= L) a[i] = INT32_MIN;
+            }
+            acc[t] = a;
+            const int bk = t * NB / TC;
+            bmax[bk] = max(bmax[bk], max(max(a[0], a[1]), max(a[2], a[3])));
+        }
+    }
+}
+
+template <int TC, int NB, int KSTEP, int MAXSTEPS, int MAXW>
+__global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__restrict__ Qt,
+                                                     const int8_t *__restrict__ Kt,
+                                                     int32_t *__restrict__ idx, int L, int k, int keep,
+                                                     int vec, int nchunks, int tiles_per_head, int hc_log2)
+{
+    typedef Mfma<KSTEP> M;
+    static_assert(TC % 8 == 0 && TC % NB == 0, "tile counts");
+    constexpr int WPH = TC / 8;                  // bitmap words per holder and chunk
+    extern __shared__ int smem[];
+    const int W = blockDim.x >> 6;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wavefront index, scalar
+    const int c = lane & 15, g = lane >> 4;
+    const int NBT = 4 * W * NB;                  // bucket maxima per unit and chunk
+    const int chunk_keys = kTileUnits * W * TC;
+    const int NW = nchunks * (chunk_keys / 32);  // bitmap words per unit
+    const int HC = 1 << hc_log2;                 // slots of one holder's segment
+    const int NHT = nchunks * 4 * W;             // holders per unit over all chunks
+    const int SL = NHT << hc_log2;               // segment slots per unit
+    // Per-unit arrays use odd strides (length + 1) so that the 16 units of a wavefront instruction
+    // fall into different LDS banks.
+    const int NBTp = NBT + 1, NWp = NW + 1, NHTp = NHT + 1;
+    int *T0s = smem;                                                            // [16]
+    int *seg = T0s + kTileUnits;                                                // [16][NHT][HC]
+    unsigned *bitmap = reinterpret_cast<unsigned *>(seg + kTileUnits * SL);     // [16][NW+1]
+    int *cnts = reinterpret_cast<int *>(bitmap + kTileUnits * NWp);             // [16][NHT+1]
+    int *bm = cnts + kTileUnits * NHTp;                                         // [16][NBT+1], phases A-B
+    int2 *compact = reinterpret_cast<int2 *>(bm) + w * kCompactCap;             // per wavefront, phase D:
+                                                                                // reuses the bm storage
+
+    const unsigned tile = xcd_contiguous(blockIdx.x, gridDim.x);
+    const unsigned n = tile / (unsigned)tiles_per_head;
+    const int u0 = (int)(tile % (unsigned)tiles_per_head) * kTileUnits;
+    const int G = L / vec;
+    const int Ka = vec * k;
+    const int nsteps = (Ka + KSTEP - 1) / KSTEP;
+    const int8_t *Kh = Kt + (size_t)n * L * k;
+    const int8_t *Qh = Qt + (size_t)n * L * k;   // unit u occupies bytes [u*Ka, u*Ka + Ka)
+
+    // B operand: unit u0+c, piece g of every contraction step.  Key operand offsets per step.
+    typename M::op_t qop[MAXSTEPS];
+    int koff[MAXSTEPS];
+    const bool unit_live = u0 + c < G;
+#pragma unroll
+    for (int s = 0; s < MAXSTEPS; ++s) {
+        const int m = KSTEP * s + M::kBytes * g;
+        const bool ok = s < nsteps && m < Ka;
+        qop[s] = (ok && unit_live) ? M::load(Qh + (size_t)(u0 + c) * Ka + m) : M::zero();
+        koff[s] = ok ? m % k : 0;
+    }
+    // the key operand repeats from step to step when k divides the step width
+    const bool same_kop = (KSTEP % k) == 0;
+
+    if (threadIdx.x < kTileUnits) T0s[threadIdx.x] = kAllCandidates;
+    __syncthreads();
+
+    PHASE_START();
+    for (int chunk = 0; chunk < nchunks; ++chunk) {
+        const int chunk_base = chunk * chunk_keys;
+        const int wave_lo = chunk_base + w * kTileUnits * TC;          // first key of this wavefront
+        const int out_lo = wave_lo + g * 4 * TC;                        // first key of this lane's stream
+        const int op_lo = wave_lo + (c >> 2) * 4 * TC + (c & 3);        // operand row c of tile 0
+        v4i acc[TC];
+        int bmax[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) bmax[b] = INT32_MIN;
+
+        if (wave_lo < L) {
+            if (wave_lo + kTileUnits * TC > L)
+                score_chunk<TC, NB, KSTEP, MAXSTEPS, true>(acc, bmax, Kh, k, L, op_lo, out_lo, nsteps, same_kop,
+                                                          qop, koff);
+            else
+                score_chunk<TC, NB, KSTEP, MAXSTEPS, false>(acc, bmax, Kh, k, L, op_lo, out_lo, nsteps,
+                                                           same_kop, qop, koff);
+        } else {
+#pragma unroll
+            for (int t = 0; t < TC; ++t) acc[t] = v4i{INT32_MIN, INT32_MIN, INT32_MIN, INT32_MIN};
+        }
+
+        // (B) lower bound T0 per unit from the bucket maxima
+#pragma unroll
+        for (int b = 0; b < NB; ++b) bm[c * NBTp + (4 * w + g) * NB + b] = bmax[b];
+        PHASE_MARK(0);
+        if (DSA_PREDICT_STOP == 1) continue;
+        __syncthreads();
+        PHASE_MARK(1);
+        for (int uu = w; uu < kTileUnits; uu += W) {
+            const int *v = bm + uu * NBTp;
+            constexpr int VB = NB * MAXW / 16;  // NBT <= 4 * MAXW * NB values over 64 lanes
+            int vb[VB];
+#pragma unroll
+            for (int i = 0; i < VB; ++i) vb[i] = v[min(i * kWave + lane, NBT - 1)];
+            int lo = INT32_MAX, hi = INT32_MIN, real = 0;
+#pragma unroll
+            for (int i = 0; i < VB; ++i) {
+                if (i * kWave + lane >= NBT) vb[i] = INT32_MIN;
+                if (vb[i] != INT32_MIN) lo = min(lo, vb[i]);      // buckets of padding keys hold INT32_MIN
+                hi = max(hi, vb[i]);
+                real += __popcll(__ballot(vb[i] != INT32_MIN));
+            }
+            int T = INT32_MIN;
+            if (real >= keep) T = kth_largest<VB>(vb, keep, wave_min(lo), wave_max(hi));
+            if (lane == 0) T0s[uu] = max(T0s[uu], T);
+        }
+        PHASE_MARK(2);
+        if (DSA_PREDICT_STOP == 2) continue;
+        __syncthreads();
+        PHASE_MARK(3);
+
+        // (C) candidates: bit j of a unit's bitmap = score(unit, key j) >= T0; passing scores are
+        // appended, in key order, to this holder's segment.
+        const int T0 = T0s[c];
+        const int holder = chunk * 4 * W + 4 * w + g;
+        int *myseg = seg + c * SL + (holder << hc_log2);
+        // entry o sits in slot (o + rot) % HC; the rotation spreads the lanes of this instruction, and
+        // the lanes that later read one unit's segments, over the LDS banks
+        const int rot = lane + (holder >> 2);
+        unsigned *words = bitmap + c * NWp + out_lo / 32;
+        int pos0 = 0;
+#pragma unroll
+        for (int q = 0; q < WPH; ++q) {
+            unsigned word = 0;
+            int pos = pos0;
+#pragma unroll
+            for (int e = 0; e < 32; ++e) {
+                const int s = acc[8 * q + e / 4][e % 4];
+                myseg[(pos + rot) & (HC - 1)] = s;      // kept only if the end moves past it
+                // word = 2*word + (s >= T0): compare into the carry, add with carry
+                asm("v_cmp_ge_i32 vcc, %1, %2\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc"
+                    : "+v"(word)
+                    : "v"(s), "v"(T0)
+                    : "vcc");
+                pos = pos0 + __popc(word);
+            }
+            words[q] = __brev(word);            // the first key of the word was shifted in first
+            pos0 = pos;
+        }
+        cnts[c * NHTp + holder] = pos0;         // HC or more means the segment wrapped
+        PHASE_MARK(4);
+        // bm / T0s are rewritten only after the next chunk's first barrier
+    }
+    if (DSA_PREDICT_STOP >= 1 && DSA_PREDICT_STOP <= 3) return;
+    __syncthreads();
+    PHASE_MARK(5);
+
+    // (D) exact selection among the candidates, one wavefront per unit
+    const int k4 = k / 4;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int uu = w; uu < kTileUnits; uu += W) {
+        const int u = u0 + uu;
+        if (u >= G) break;
+        const unsigned *bw = bitmap + uu * NWp;
+        const int *cu = cnts + uu * NHTp;
+        const int *sg = seg + uu * SL;
+        const int *qu = reinterpret_cast<const int *>(Qh + (size_t)u * Ka);
+        int32_t *out = idx + ((size_t)n * G + u) * keep;
+        const int T0 = T0s[uu];
+
+        int nc = 0;
+        for (int h = lane; h < NHT; h += kWave) nc += cu[h];
+        nc = wave_sum(nc);
+        const bool fits = nc <= kCompactCap;
+        PHASE_COUNT(12, nc);
+        PHASE_COUNT(13, 1);
+
+        if (fits) {
+            // candidates in key order as (score, key) pairs; a lane takes two bitmap words per round
+            int rank_base = 0;
+            for (int w0 = 0; w0 < NW; w0 += 2 * kWave) {
+                const int wi = w0 + 2 * lane;
+                const unsigned m0 = wi < NW ? bw[wi] : 0u;
+                const unsigned m1 = wi + 1 < NW ? bw[wi + 1] : 0u;
+                const int cnt = __popc(m0) + __popc(m1);
+                int round_total;
+                const int incl = wave_incl_scan(cnt, lane, &round_total);
+                int r = rank_base + incl - cnt;
+                rank_base += round_total;
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int wj = wi + half;
+                    unsigned m = half ? m1 : m0;
+                    if (m) {
+                        const int hold = wj / WPH;
+                        int o = 0;                       // entries of this holder before word wj
+                        for (int x = hold * WPH; x < wj; ++x) o += __popc(bw[x]);
+                        const int *src = sg + (hold << hc_log2);
+                        // HC or more hits: the segment wrapped and a later non-candidate overwrote its
+                        // first entry; such a holder's few scores are recomputed instead
+                        const bool wrapped = cu[hold] >= HC;
+                        o += uu + 16 * (hold & 3) + (hold >> 2);     // the writer's rotation
+                        while (m) {
+                            const int bit = __ffs(m) - 1;
+                            m &= m - 1;
+                            const int key = wj * 32 + bit;
+                            const int sc1 = wrapped ? unit_key_score(qu, Kh + (size_t)key * k, vec, k4)
+                                                    : src[o & (HC - 1)];
+                            ++o;
+                            compact[r++] = make_int2(sc1, key);
+                        }
+                    }
+                }
+            }
+            wave_lds_sync();
+            PHASE_MARK(6);
+            constexpr int NR = kCompactCap / kWave;
+            const int groups = (nc + kWave - 1) / kWave;
+            int sc[NR], ck[NR];
+#pragma unroll
+            for (int b = 0; b < NR; ++b) {      // unconditional loads; slots past nc are blanked below
+                const int2 e = compact[b * kWave + lane];
+                sc[b] = e.x;
+                ck[b] = e.y;
+            }
+            int hi = INT32_MIN;
+#pragma unroll
+            for (int b = 0; b < NR; ++b) {
+                if (b * kWave + lane >= nc) sc[b] = INT32_MIN;
+                hi = max(hi, sc[b]);
+            }
+            PHASE_MARK(7);
+            // every candidate reaches T0 and there are at least keep of them
+            const int T = kth_largest<NR>(sc, keep, T0, wave_max(hi));
+            PHASE_MARK(8);
+            int gt = 0;
+#pragma unroll
+            for (int b = 0; b < NR; ++b)
+                if (b < groups) gt += __popcll(__ballot(sc[b] > T));
+            const int need_eq = keep - gt;
+            int out_base = 0, eq_base = 0;
+#pragma unroll
+            for (int b = 0; b < NR; ++b) {
+                if (b < groups) {
+                    const bool eq = sc[b] == T;       // T >= T0 > INT32_MIN: empty slots never match
+                    const unsigned long long meq = __ballot(eq);
+                    const bool sel = sc[b] > T || (eq && eq_base + __popcll(meq & below) < need_eq);
+                    const unsigned long long msel = __ballot(sel);
+                    if (sel) out[out_base + __popcll(msel & below)] = ck[b];
+                    out_base += __popcll(msel);
+                    eq_base += __popcll(meq);
+                }
+            }
+            wave_lds_sync();      // the next unit reuses `compact`
+            PHASE_MARK(9);
+        } else {
+            PHASE_COUNT(15, 1);
+            // Too many candidates (massive ties or a very large keep): the same steps over all keys,
+            // recomputing the score of every flagged key in every pass.
+            auto flagged_score = [&](int j) -> int {
+                if (j >= L || !((bw[j >> 5] >> (j & 31)) & 1u)) return INT32_MIN;
+                return unit_key_score(qu, Kh + (size_t)j * k, vec, k4);
+            };
+            int hi = INT32_MIN;
+            for (int j = lane; j < L; j += kWave) hi = max(hi, flagged_score(j));
+            hi = wave_max(hi);
+            int lo = T0;
+            while (lo < hi) {
+                const int mid = (int)(lo + ((long long)hi - lo + 1) / 2);
+                int ge = 0;
+                for (int j0 = 0; j0 < L; j0 += kWave) ge += __popcll(__ballot(flagged_score(j0 + lane) >= mid));
+                if (ge >= keep) lo = mid; else hi = mid - 1;
+            }
+            const int T = lo;
+            int gt = 0;
+            for (int j0 = 0; j0 < L; j0 += kWave) gt += __popcll(__ballot(flagged_score(j0 + lane) > T));
+            const int need_eq = keep - gt;
+            int out_base = 0, eq_base = 0;
+            for (int j0 = 0; j0 < L; j0 += kWave) {
+                const int j = j0 + lane;
+                const int s = flagged_score(j);
+                const bool eq = s == T;          // T >= T0 > INT32_MIN, so unflagged keys never match
+                const unsigned long long meq = __ballot(eq);
+                const bool sel = s > T || (eq && eq_base + __popcll(meq & below) < need_eq);
+                const unsigned long long msel = __ballot(sel);
+                if (sel) out[out_base + __popcll(msel & below)] = j;
+                out_base += __popcll(msel);
+                eq_base += __popcll(meq);
+            }
+        }
+    }
+    PHASE_FLUSH();
+}
+
+struct TilePlan {
+    int W, TC, NB, nchunks, kstep, maxsteps, maxw, tiles_per_head, hc_log2;
+    size_t lds;
+    bool ok;
+};
+
+TilePlan plan_tiles(const dsa_shape &sh)
+{
+    TilePlan p{};
+    const int L = sh.L;
+    const int Ka = sh.vec * sh.k;
+    p.kstep = Ka <= 32 ? 32 : 64;
+    const int nsteps = (Ka + p.kstep - 1) / p.kstep;
+    p.maxsteps = nsteps <= 1 ? 1 : nsteps <= 4 ? 4 : nsteps <= 8 ? 8 : 16;
+    // Short contractions leave room for 16 wavefronts of <= 128 registers (one unit each in the
+    // selection phases); long ones keep their unit operands in registers and run 8 wavefronts.
+    p.maxw = p.maxsteps <= 4 ? 16 : 8;
+    if (L <= 128 * p.maxw) { p.TC = 8; p.W = (L + 127) / 128; }
+    else if (L <= 256 * p.maxw) { p.TC = 16; p.W = p.maxw; }
+    else if (p.maxw == 16) { p.TC = 16; p.W = 16; }
+    else { p.TC = 32; p.W = 8; }
+    const int chunk_keys = kTileUnits * p.W * p.TC;
+    p.nchunks = (L + chunk_keys - 1) / chunk_keys;
+    // enough buckets that the bound is tight: about twice as many as kept keys
+    p.NB = 8;
+    while (p.NB < p.TC && 4 * p.W * p.NB < 2 * sh.keep) p.NB *= 2;
+    p.tiles_per_head = (L / sh.vec + kTileUnits - 1) / kTileUnits;
+    const int NHT = p.nchunks * 4 * p.W;
+    p.hc_log2 = 5;                                   // at most 32 slots per holder ...
+    while (p.hc_log2 > 0 && (NHT << p.hc_log2) > kSegSlots) --p.hc_log2;   // ... and kSegSlots per unit
+    const size_t NW = (size_t)p.nchunks * chunk_keys / 32;
+    auto lds_bytes = [&](int nb, int hcl) {
+        const size_t bm_bytes = sizeof(int) * (size_t)kTileUnits * (4 * p.W * nb + 1);
+        const size_t compact_bytes = sizeof(int2) * (size_t)p.W * kCompactCap;      // shares bm's storage
+        return sizeof(int) * (kTileUnits + kTileUnits * (NW + 1) + ((size_t)kTileUnits * NHT << hcl) +
+                              (size_t)kTileUnits * (NHT + 1)) +
+               (bm_bytes > compact_bytes ? bm_bytes : compact_bytes);
+    };
+    while (lds_bytes(p.NB, p.hc_log2) > kLdsBudget && (p.NB > 8 || p.hc_log2 > 0)) {
+        if (p.NB > 8) p.NB /= 2; else --p.hc_log2;
+    }
+    p.lds = lds_bytes(p.NB, p.hc_log2);
+    p.ok = p.lds <= kLdsBudget;
+    return p;
+}
+
+template <int TC, int NB, int KSTEP, int MAXSTEPS, int MAXW>
+hipError_t launch_tiles_t(const TilePlan &p, const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt,
+                          int32_t *idx, hipStream_t st)
+{
+    auto kern = predict_tiles<TC, NB, KSTEP, MAXSTEPS, MAXW>;
+    if (p.lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds);
+        if (e != hipSuccess) return e;
+    }
+    const unsigned tiles = (unsigned)sh.B * sh.H * p.tiles_per_head;
+    hipLaunchKernelGGL(kern, dim3(tiles), dim3(p.W * kWave), p.lds, st, Qt, Kt, idx, sh.L, sh.k, sh.keep,
+                       sh.vec, p.nchunks, p.tiles_per_head, p.hc_log2);
+    return hipGetLastError();
+}
+
+template <int TC, int NB>
+hipError_t launch_tiles_k(const TilePlan &p, const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt,
+                          int32_t *idx, hipStream_t st)
+{
+    if constexpr (TC <= 16) {
+        if (p.kstep == 32) return launch_tiles_t<TC, NB, 32, 1, 16>(p, sh, Qt, Kt, idx, st);
+        if (p.maxsteps == 1) return launch_tiles_t<TC, NB, 64, 1, 16>(p, sh, Qt, Kt, idx, st);
+        if (p.maxsteps == 4) return launch_tiles_t<TC, NB, 64, 4, 16>(p, sh, Qt, Kt, idx, st);
+    }
+    if (p.maxsteps == 8) return launch_tiles_t<TC, NB, 64, 8, 8>(p, sh, Qt, Kt, idx, st);
+    return launch_tiles_t<TC, NB, 64, 16, 8>(p, sh, Qt, Kt, idx, st);
+}
+
+hipError_t launch_tiles(const TilePlan &p, const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt,
+                        int32_t *idx, hipStream_t st)
+{
+    if (p.TC == 8) return launch_tiles_k<8, 8>(p, sh, Qt, Kt, idx, st);
+    if (p.TC == 16) return p.NB == 8 ? launch_tiles_k<16, 8>(p, sh, Qt, Kt, idx, st)
+                                     : launch_tiles_k<16, 16>(p, sh, Qt, Kt, idx, st);
+    if (p.NB == 8) return launch_tiles_k<32, 8>(p, sh, Qt, Kt, idx, st);
+    if (p.NB == 16) return launch_tiles_k<32, 16>(p, sh, Qt, Kt, idx, st);
+    return launch_tiles_k<32, 32>(p, sh, Qt, Kt, idx, st);
+}
+
 // Row maximum of the approximate scores with the int8 matrix cores.  A wavefront keeps 32 query
 // rows as the B operand of v_mfma_i32_32x32x32_i8 and sweeps the keys 32 at a time as the A
 // operand, so each lane ends up with one query column and 16 key rows per tile: the running
@@ -177,6 +760,17 @@ __global__ __launch_bounds__(256) void rowmax_mfma(const int8_t *__restrict__ Qt
 
 }  // namespace
 
+#ifdef DSA_PHASE_TIMING
+extern "C" void dsa_debug_phase_cycles(unsigned long long *host16, int reset)
+{
+    if (host16) (void)hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_phase_cycles), sizeof(g_phase_cycles));
+    if (reset) {
+        unsigned long long z[16] = {0};
+        (void)hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), z, sizeof(z));
+    }
+}
+#endif
+
 int predict_max_L() { return kUnitMaxL; }
 
 size_t predict_workspace_bytes(const dsa_shape &) { return 0; }
@@ -184,6 +778,12 @@ size_t predict_workspace_bytes(const dsa_shape &) { return 0; }
 hipError_t launch_predict(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *idx, void *,
                           hipStream_t st)
 {
+    static const bool use_unit_kernel = [] {
+        const char *e = getenv("DSA_PREDICT_IMPL");
+        return e && e[0] == 'u';
+    }();
+    const TilePlan plan = plan_tiles(sh);
+    if (!use_unit_kernel && plan.ok) return launch_tiles(plan, sh, Qt, Kt, idx, st);
     const unsigned units = (unsigned)sh.B * sh.H * (sh.L / sh.vec);
     const size_t lds = ((size_t)sh.L + sh.vec * (sh.k / 4) + 8) * sizeof(int);
     if (sh.vec == 1) {
