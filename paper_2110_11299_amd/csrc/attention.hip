@@ -147,6 +147,144 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
     }
 }
 
+// Group kernel for the vector-wise mask with bfloat16 inputs.  The 8 query rows of a group share
+// one key list, so each gathered key / value row serves 8 rows and the products become small
+// dense contractions for the bf16 matrix cores (v_mfma_f32_16x16x32_bf16, fp32 accumulate).  One
+// wavefront owns one group.
+//   Scores: the gathered key rows are the A operand (16 keys per tile, loaded straight from
+//   global memory as 16-byte pieces: lane (r = lane%16, g = lane/16) holds key r, elements
+//   [8g, 8g+8) of each 32-element step), the 8 query rows (padded to 16) the B operand.  Lane
+//   (c, g) then owns, for query c, keys 4g..4g+3 of the tile.  Scaled scores go to LDS.
+//   Output: weights stay in the lane that owns them.  Over a 32-key step lane group g owns keys
+//   {4g+i} of the first tile and {16+4g+i} of the second: these 8 are its slots of the step's
+//   contraction index, so its packed bf16 weights ARE the A operand (query c, slots of g).  The
+//   32 gathered value rows go through LDS once and come back transposed as the B operand with
+//   the same slot order (lane (c, g): column c of the rows that are g's slots).
+// The weights are rounded to bfloat16 for the second product (relative 2^-9, inside the 2e-2
+// budget of bfloat16 inputs); scores, softmax statistics and accumulation are fp32.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int kGroupWaves = 4;
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int D>
+__global__ __launch_bounds__(kGroupWaves *kWave) void attention_groups_bf16(
+    const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
+    const int32_t *__restrict__ idx, float *__restrict__ O, int L, int keep, int keep_pad, float scale,
+    unsigned total_groups)
+{
+    constexpr int KS = D / 32;             // contraction steps of Q K^T
+    constexpr int CT = D / 16;             // 16-column tiles of the output
+    constexpr int VROW = D * 2 + 16;       // bytes of one value row in LDS (padded against bank conflicts)
+    constexpr int LPR = D / 8;             // lanes that load one row as 16-byte pieces
+    constexpr int RPI = kWave / LPR;       // rows per load instruction
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int c = lane & 15, g = lane >> 4;
+    const size_t per_wave = (size_t)8 * keep_pad * sizeof(float) + 32 * VROW;
+    float *sS = reinterpret_cast<float *>(lds_raw + wave * per_wave);          // [8][keep_pad]
+    char *sV = reinterpret_cast<char *>(sS + 8 * keep_pad);                    // [32][VROW]
+
+    const unsigned vblock = xcd_contiguous(blockIdx.x, gridDim.x);
+    const unsigned grp = vblock * kGroupWaves + wave;
+    const bool live = grp < total_groups;
+    const unsigned gi = live ? grp : total_groups - 1;     // dead waves shadow a real group, write nothing
+    const unsigned G = L / 8, n = gi / G, u = gi % G;
+    const int32_t *list = idx + (size_t)gi * keep;
+    const uint16_t *Kh = K + (size_t)n * L * D, *Vh = V + (size_t)n * L * D;
+
+    bf16x8 qop[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        const uint4 raw = c < 8 ? *reinterpret_cast<const uint4 *>(Q + ((size_t)n * L + u * 8 + c) * D + 32 * s + 8 * g)
+                                : make_uint4(0, 0, 0, 0);
+        qop[s] = __builtin_bit_cast(bf16x8, raw);
+    }
+
+    // scores of all kept keys -> LDS, running maximum per query
+    float mx = -INFINITY;
+    for (int t0 = 0; t0 < keep_pad; t0 += 16) {
+        const int j = min(max(list[min(t0 + c, keep - 1)], 0), L - 1);
+        const uint16_t *krow = Kh + (size_t)j * D + 8 * g;
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const bf16x8 kop = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(krow + 32 * s));
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qop[s], acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[i] = t0 + 4 * g + i < keep ? acc[i] * scale : -INFINITY;
+            mx = fmaxf(mx, acc[i]);
+        }
+        if (c < 8) *reinterpret_cast<v4f *>(sS + c * keep_pad + t0 + 4 * g) = acc;
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    wave_lds_fence();
+
+    v4f o[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) o[ct] = v4f{0.f, 0.f, 0.f, 0.f};
+    float z = 0.f;
+    const float *srow = sS + (c & 7) * keep_pad + 4 * g;
+    for (int t0 = 0; t0 < keep_pad; t0 += 32) {
+        // 32 gathered value rows -> LDS
+#pragma unroll
+        for (int rr = 0; rr < 32 / RPI; ++rr) {
+            const int row = rr * RPI + lane / LPR, piece = lane % LPR;
+            const int j = min(max(list[min(t0 + row, keep - 1)], 0), L - 1);
+            const uint4 raw = *reinterpret_cast<const uint4 *>(Vh + (size_t)j * D + piece * 8);
+            *reinterpret_cast<uint4 *>(sV + row * VROW + piece * 16) = raw;
+        }
+        // weights of this lane's 8 slots
+        const v4f s0 = *reinterpret_cast<const v4f *>(srow + t0);
+        const v4f s1 = *reinterpret_cast<const v4f *>(srow + t0 + 16);
+        bf16x8 pa;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float p0 = __expf(s0[i] - mx), p1 = __expf(s1[i] - mx);
+            z += p0 + p1;
+            pa[i] = (__bf16)p0;
+            pa[4 + i] = (__bf16)p1;
+        }
+        wave_lds_fence();
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            bf16x8 vb;
+            const char *col = sV + (16 * ct + c) * 2;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                vb[i] = *reinterpret_cast<const __bf16 *>(col + (4 * g + i) * VROW);
+                vb[4 + i] = *reinterpret_cast<const __bf16 *>(col + (16 + 4 * g + i) * VROW);
+            }
+            o[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, vb, o[ct], 0, 0, 0);
+        }
+        wave_lds_fence();       // the next step overwrites the value tile
+    }
+    z += __shfl_xor(z, 16, kWave);
+    z += __shfl_xor(z, 32, kWave);
+    // lane (c, g) holds O[query 4g+i][16 ct + c]; the sum of query q sits in the lanes with column q
+    if (live) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float inv = 1.f / __shfl(z, (4 * g + i) & 7, kWave);
+            if (g < 2) {
+                float *out = O + ((size_t)n * L + u * 8 + 4 * g + i) * D + c;
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) out[16 * ct] = o[ct][i] * inv;
+            }
+        }
+    }
+}
+
 // Softmax over the `keep` scores of each row: one wavefront per row.
 __global__ __launch_bounds__(kRowWaves *kWave) void softmax_rows(const float *S, float *P, int keep,
                                                                   unsigned total_rows)
@@ -193,6 +331,32 @@ hipError_t launch_rows(AttnMode mode, const dsa_shape &sh, const void *Q, const 
     return hipGetLastError();
 }
 
+// LDS of one workgroup of the group kernel: per wavefront 8 rows of scores and a 32-row value tile.
+size_t groups_lds_bytes(const dsa_shape &sh)
+{
+    const size_t keep_pad = (size_t)(sh.keep + 31) / 32 * 32;
+    return kGroupWaves * (8 * keep_pad * sizeof(float) + 32 * ((size_t)sh.d * 2 + 16));
+}
+
+template <int D>
+hipError_t launch_groups(const dsa_shape &sh, const void *Q, const void *K, const void *V, const int32_t *idx,
+                         float *O, hipStream_t st)
+{
+    const unsigned groups = (unsigned)sh.B * sh.H * (sh.L / 8);
+    const int keep_pad = (sh.keep + 31) / 32 * 32;
+    const size_t lds = groups_lds_bytes(sh);
+    auto kern = attention_groups_bf16<D>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3((groups + kGroupWaves - 1) / kGroupWaves), dim3(kGroupWaves * kWave), lds, st,
+                       static_cast<const uint16_t *>(Q), static_cast<const uint16_t *>(K),
+                       static_cast<const uint16_t *>(V), idx, O, sh.L, sh.keep, keep_pad, sh.scale, groups);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 int attention_max_keep() { return kMaxKeep; }
@@ -204,6 +368,10 @@ hipError_t launch_attention(AttnMode mode, const dsa_shape &sh, const void *Q, c
     if (sh.dtype == DSA_F32) {
         if (sh.d == 64) return launch_rows<float, 64>(mode, sh, Q, K, V, idx, Pin, S, O, st);
         return launch_rows<float, 128>(mode, sh, Q, K, V, idx, Pin, S, O, st);
+    }
+    if (mode == kFused && sh.vec == 8 && groups_lds_bytes(sh) <= 144 * 1024) {
+        if (sh.d == 64) return launch_groups<64>(sh, Q, K, V, idx, O, st);
+        return launch_groups<128>(sh, Q, K, V, idx, O, st);
     }
     if (sh.d == 64) return launch_rows<uint16_t, 64>(mode, sh, Q, K, V, idx, Pin, S, O, st);
     return launch_rows<uint16_t, 128>(mode, sh, Q, K, V, idx, Pin, S, O, st);
