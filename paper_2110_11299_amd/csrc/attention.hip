@@ -174,8 +174,11 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// (The launch bound is twice the launched size: with at most 256 registers per lane the compiler
+// gives the matrix core plain VGPR destinations instead of accumulation registers that every
+// other instruction would have to copy from.)
 template <int D>
-__global__ __launch_bounds__(kGroupWaves *kWave) void attention_groups_bf16(
+__global__ __launch_bounds__(2 * kGroupWaves *kWave) void attention_groups_bf16(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int32_t *__restrict__ idx, float *__restrict__ O, int L, int keep, int keep_pad, float scale,
     unsigned total_groups)

@@ -705,57 +705,115 @@ hipError_t launch_tiles(const TilePlan &p, const dsa_shape &sh, const int8_t *Qt
     return launch_tiles_k<32, 32>(p, sh, Qt, Kt, idx, st);
 }
 
-// Row maximum of the approximate scores with the int8 matrix cores.  A wavefront keeps 32 query
-// rows as the B operand of v_mfma_i32_32x32x32_i8 and sweeps the keys 32 at a time as the A
-// operand, so each lane ends up with one query column and 16 key rows per tile: the running
-// maximum is a per-lane scalar, reduced across the two lane halves at the end.
-template <int KSTEPS>   // k padded to 32 * KSTEPS
-__global__ __launch_bounds__(256) void rowmax_mfma(const int8_t *__restrict__ Qt,
-                                                   const int8_t *__restrict__ Kt,
-                                                   int32_t *__restrict__ rowmax, int L, int k,
-                                                   unsigned N)
+// Row maximum of the approximate scores with the int8 matrix cores: the contraction with the
+// smallest consumer that still looks at every score.  A wavefront keeps 64 query rows as two B
+// operands of v_mfma_i32_32x32x32_i8 and sweeps its share of the keys 32 at a time as the A
+// operand, so each lane ends up with one query column per operand and 16 key rows per tile: the
+// running maximum is a per-lane scalar.  Key tiles are prefetched several tiles ahead into a
+// register ring, and the maxima of tile t are taken (two scores per v_max3) while the matrix
+// core works on tile t+1.  KSPLIT wavefronts share one 64-row query tile and split the keys, so
+// that a SIMD holds several wavefronts and one's v_max3 stream fills the other's matrix-core
+// time; they combine through LDS at the end.
+// (The launch bound is at least 512 threads: with at most 256 registers per lane the compiler
+// gives the matrix core plain VGPR destinations that v_max3 can read directly.)
+template <int KSTEPS, int KSPLIT>   // k padded to 32 * KSTEPS
+__global__ __launch_bounds__(KSPLIT <= 2 ? 512 : 256 * KSPLIT) void rowmax_mfma(
+    const int8_t *__restrict__ Qt, const int8_t *__restrict__ Kt, int32_t *__restrict__ rowmax, int L, int k,
+    unsigned N)
 {
+    constexpr int PD = (KSPLIT <= 2 ? 8 : 4) / KSTEPS;   // prefetch depth in tiles (KSTEPS <= 4)
+    __shared__ int part[4 * KSPLIT][64];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int col = lane & 31, half = lane >> 5;
-    const unsigned tiles_per_head = (L + 31) / 32;
-    const unsigned qtile = blockIdx.x * 4 + wave;
-    const unsigned n = qtile / tiles_per_head, i0 = (qtile % tiles_per_head) * 32;
-    if (n >= N) return;
+    const int qslot = wave / KSPLIT, ks = wave % KSPLIT;
+    const unsigned qtiles_per_head = (L + 63) / 64;
+    const unsigned qtile = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + qslot;
+    const bool live = qtile < N * qtiles_per_head;
+    const unsigned n = live ? qtile / qtiles_per_head : 0;
+    const int i0 = live ? (int)(qtile % qtiles_per_head) * 64 : 0;
     const int8_t *Qh = Qt + (size_t)n * L * k, *Kh = Kt + (size_t)n * L * k;
 
-    // operand piece of this lane: 16 consecutive c at 32*step + 16*half; zero beyond k or L
-    v4i qop[KSTEPS];
-    const int qi = i0 + col;
+    // operand piece of this lane: 16 consecutive c at 32*step + 16*half.  Beyond k (and, for
+    // queries, beyond L) the query piece is zero, so the key piece there may hold anything and is
+    // read from offset 0.  Key rows beyond L are read from row L-1 and masked at the end.
+    int coff[KSTEPS];
+    v4i qop[2][KSTEPS];
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) {
         const int c = 32 * s + 16 * half;
-        qop[s] = (qi < L && c < k) ? *reinterpret_cast<const v4i *>(Qh + (size_t)qi * k + c) : v4i{0, 0, 0, 0};
+        coff[s] = c < k ? c : 0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int qi = i0 + 32 * h + col;
+            qop[h][s] = (qi < L && c < k) ? *reinterpret_cast<const v4i *>(Qh + (size_t)qi * k + c) : v4i{0, 0, 0, 0};
+        }
     }
-    int m = INT32_MIN;
-    for (int j0 = 0; j0 < L; j0 += 32) {
-        const int j = j0 + col;
-        v16i acc = {0};
+    const int T = (L + 31) / 32;                       // key tiles in all
+    const int Tper = (T + KSPLIT - 1) / KSPLIT;
+    const int ta = ks * Tper, tb = min(T, ta + Tper);  // this wavefront's tiles
+    auto load_tile = [&](int t, v4i (&dst)[KSTEPS]) {
+        const int8_t *row = Kh + (size_t)min(32 * t + col, L - 1) * k;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) dst[s] = *reinterpret_cast<const v4i *>(row + coff[s]);
+    };
+    v4i ring[PD][KSTEPS];
+#pragma unroll
+    for (int p = 0; p < PD; ++p) load_tile(min(ta + p, T - 1), ring[p]);
+
+    int m0 = INT32_MIN, m1 = INT32_MIN;
+    v16i pa, pb;           // scores of the previous tile, reduced while the next one is computed
+#pragma unroll
+    for (int r = 0; r < 16; ++r) pa[r] = pb[r] = INT32_MIN;
+    auto step = [&](v4i (&kop)[KSTEPS]) {
+        v16i a = {0}, b = {0};
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) {
-            const int c = 32 * s + 16 * half;
-            const v4i kop = (j < L && c < k) ? *reinterpret_cast<const v4i *>(Kh + (size_t)j * k + c)
-                                             : v4i{0, 0, 0, 0};
-            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop, qop[s], acc, 0, 0, 0);
+            a = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[s], qop[0][s], a, 0, 0, 0);
+            b = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[s], qop[1][s], b, 0, 0, 0);
         }
-        // register r of this lane is key row 8*(r/4) + 4*half + r%4 of the tile
-        if (j0 + 32 <= L) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) m = max(m, acc[r]);
-        } else {
+        for (int r = 0; r < 16; r += 2) {
+            m0 = max(max(pa[r], pa[r + 1]), m0);
+            m1 = max(max(pb[r], pb[r + 1]), m1);
+        }
+        pa = a;
+        pb = b;
+    };
+    // all tiles but the last of the sweep hold only real keys; the ring slot of tile t is (t - ta) % PD
+    int t = ta;
+    for (; t + PD <= tb - 1; t += PD) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int jr = j0 + 8 * (r / 4) + 4 * half + (r % 4);
-                if (jr < L) m = max(m, acc[r]);
+        for (int p = 0; p < PD; ++p) {
+            step(ring[p]);
+            load_tile(min(t + p + PD, T - 1), ring[p]);
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < PD; ++p)
+        if (t + p < tb) step(ring[p]);      // the rest; pa, pb end up as tile tb-1
+    // that tile may reach past L: register r of this lane is key row 8*(r/4) + 4*half + r%4 of it
+    if (ta < tb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            if (32 * (tb - 1) + 8 * (r / 4) + 4 * half + (r % 4) < L) {
+                m0 = max(m0, pa[r]);
+                m1 = max(m1, pb[r]);
             }
         }
     }
-    m = max(m, __shfl_xor(m, 32, kWave));
-    if (half == 0 && qi < L) rowmax[(size_t)n * L + qi] = m;
+    m0 = max(m0, __shfl_xor(m0, 32, kWave));
+    m1 = max(m1, __shfl_xor(m1, 32, kWave));
+    if (half == 0) {
+        part[wave][col] = m0;
+        part[wave][32 + col] = m1;
+    }
+    __syncthreads();
+    if (ks == 0 && live) {
+        int m = part[wave][lane];
+#pragma unroll
+        for (int j = 1; j < KSPLIT; ++j) m = max(m, part[wave + j][lane]);
+        if (i0 + lane < L) rowmax[(size_t)n * L + i0 + lane] = m;
+    }
 }
 
 }  // namespace
@@ -806,20 +864,34 @@ hipError_t launch_predict(const dsa_shape &sh, const int8_t *Qt, const int8_t *K
     return hipGetLastError();
 }
 
+template <int KSTEPS>
+hipError_t launch_rowmax_k(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *rowmax, hipStream_t st)
+{
+    const unsigned N = (unsigned)sh.B * sh.H;
+    const unsigned qtiles = N * ((sh.L + 63) / 64);
+    const dim3 grid((qtiles + 3) / 4);
+    // enough wavefronts for about four per SIMD (1024 SIMDs), but at least 8 key tiles each
+    const int tiles = (sh.L + 31) / 32;
+    int ksplit = 1;
+    while (ksplit < 4 && (size_t)qtiles * ksplit < 4096 && tiles / (2 * ksplit) >= 8) ksplit *= 2;
+    if (ksplit == 1)
+        hipLaunchKernelGGL((rowmax_mfma<KSTEPS, 1>), grid, dim3(256), 0, st, Qt, Kt, rowmax, sh.L, sh.k, N);
+    else if (ksplit == 2)
+        hipLaunchKernelGGL((rowmax_mfma<KSTEPS, 2>), grid, dim3(512), 0, st, Qt, Kt, rowmax, sh.L, sh.k, N);
+    else
+        hipLaunchKernelGGL((rowmax_mfma<KSTEPS, 4>), grid, dim3(1024), 0, st, Qt, Kt, rowmax, sh.L, sh.k, N);
+    return hipGetLastError();
+}
+
 hipError_t launch_rowmax(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *rowmax,
                          hipStream_t st)
 {
-    const unsigned N = (unsigned)sh.B * sh.H;
-    const unsigned qtiles = N * ((sh.L + 31) / 32);
-    const dim3 grid((qtiles + 3) / 4), block(256);
-    const int ksteps = (sh.k + 31) / 32;
-    switch (ksteps) {
-    case 1: hipLaunchKernelGGL(rowmax_mfma<1>, grid, block, 0, st, Qt, Kt, rowmax, sh.L, sh.k, N); break;
-    case 2: hipLaunchKernelGGL(rowmax_mfma<2>, grid, block, 0, st, Qt, Kt, rowmax, sh.L, sh.k, N); break;
-    case 3: hipLaunchKernelGGL(rowmax_mfma<3>, grid, block, 0, st, Qt, Kt, rowmax, sh.L, sh.k, N); break;
-    default: hipLaunchKernelGGL(rowmax_mfma<4>, grid, block, 0, st, Qt, Kt, rowmax, sh.L, sh.k, N); break;
+    switch ((sh.k + 31) / 32) {
+    case 1: return launch_rowmax_k<1>(sh, Qt, Kt, rowmax, st);
+    case 2: return launch_rowmax_k<2>(sh, Qt, Kt, rowmax, st);
+    case 3: return launch_rowmax_k<3>(sh, Qt, Kt, rowmax, st);
+    default: return launch_rowmax_k<4>(sh, Qt, Kt, rowmax, st);
     }
-    return hipGetLastError();
 }
 
 }  // namespace dsa
