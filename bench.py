@@ -31,6 +31,7 @@ INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 # HBM traffic of one launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this command (see profiles/); None until measured.
 MEASURED_TRAFFIC_BYTES = None
+PMC_COPY_BYTES = 256 << 20   # size of the calibration copy in --pmc-mode
 
 
 def gather_bytes(cfg) -> int:
@@ -48,6 +49,11 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time every stage on the other workload configs (adds 'all_configs' to the line)")
+    ap.add_argument("--pmc-mode", action="store_true",
+                    help="for rocprofv3 --pmc runs: a few steps plus one plain device copy of known size "
+                         "(calibrates FETCH_SIZE / WRITE_SIZE), no other output")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (every head*sequence is an independent problem and "
@@ -86,6 +92,16 @@ def main() -> int:
     def step():
         for p in passes:
             pkg.dsa_attention_fwd(p["sh"], Q, K, V, Qt, Kt, O=p["O"], idx_out=p["idx"], ws=p["ws"])
+
+    if args.pmc_mode:
+        for _ in range(3):
+            step()
+        src = torch.empty(PMC_COPY_BYTES, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads and writes PMC_COPY_BYTES each
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_mode": True, "copy_bytes": PMC_COPY_BYTES}))
+        return 0
 
     for _ in range(args.warmup):
         step()
@@ -141,10 +157,36 @@ def main() -> int:
                     frac=dom["attention_frac_hbm"], traffic=MEASURED_TRAFFIC_BYTES,
                     algorithmic_bytes=gather_bytes(cf), avg_launch_ms=dom["attention_ms"])
 
+    all_configs = None
+    if args.all_configs:
+        all_configs = {}
+        for name in ("C1", "C2", "C3", "C5"):
+            cfg = di.CONFIGS[name]
+            y = di.make_inputs(cfg)
+            if cfg.dtype == "bf16":
+                q, kk, v = (torch.from_numpy(y.storage(t).view(np.int16)).cuda().view(torch.bfloat16) for t in "QKV")
+            else:
+                q, kk, v = (torch.from_numpy(y.storage(t)).cuda() for t in "QKV")
+            qt, kt = torch.from_numpy(y.Qt).cuda(), torch.from_numpy(y.Kt).cuda()
+            shc = pkg.make_shape(cfg.B, cfg.H, cfg.L, cfg.d, cfg.k, cfg.keep, cfg.vec,
+                                 pkg.DSA_F32 if cfg.dtype == "f32" else pkg.DSA_BF16, float(cfg.scale))
+            o = torch.empty((cfg.B, cfg.H, cfg.L, cfg.d), dtype=torch.float32, device="cuda")
+            ix = torch.empty((cfg.B, cfg.H, cfg.L // cfg.vec, cfg.keep), dtype=torch.int32, device="cuda")
+            wsc = pkg.binding.alloc_workspace(shc)
+            pkg.dsa_attention_fwd(shc, q, kk, v, qt, kt, O=o, idx_out=ix, ws=wsc)
+            st = dict(predict_ms=timed(lambda: pkg.dsa_predict_mask(shc, qt, kt, idx=ix, ws=wsc), reps),
+                      attention_ms=timed(lambda: pkg.dsa_masked_attention(shc, q, kk, v, ix, O=o), reps),
+                      fwd_ms=timed(lambda: pkg.dsa_attention_fwd(shc, q, kk, v, qt, kt, O=o, idx_out=ix, ws=wsc), reps))
+            st["heads_seqs_per_s"] = cfg.N / (st["fwd_ms"] * 1e-3)
+            st["attention_gather_GBs"] = gather_bytes(cfg) / (st["attention_ms"] * 1e-3) / 1e9
+            st["predict_int8_TOPS"] = 2.0 * cfg.N * cfg.L * cfg.L * cfg.k / (st["predict_ms"] * 1e-3) / 1e12
+            all_configs[name] = st
+            del q, kk, v, qt, kt, o, ix, wsc
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import dsa_oracle
-        heads = 4
+        heads = cf.N
         sl = slice(0, heads)
         Qf, Kf, Vf = (a.reshape(cf.N, cf.L, cf.d)[sl] for a in (x.Q, x.K, x.V))
         Qtf, Ktf = (a.reshape(cf.N, cf.L, cf.k)[sl] for a in (x.Qt, x.Kt))
@@ -155,8 +197,8 @@ def main() -> int:
         t_cpu = time.perf_counter() - t0
         cpu_baseline = dict(value=2 * heads / t_cpu, unit="heads*seqs/s", cores=dsa_oracle.num_threads(),
                             kind="oracle", seconds=t_cpu,
-                            sample=f"first {heads} of {cf.N} heads*seqs of the same tensors, fine-grained pass "
-                                   f"then vector-wise pass, plain C oracle with OpenMP over units")
+                            sample=f"all {heads} heads*seqs of the same tensors, one fine-grained pass then one "
+                                   f"vector-wise pass (= one step), plain C oracle with OpenMP over units")
 
     out = dict(metric="DSA attn fwd heads*seqs/sec at L=4096, keep 5%", value=value, unit="heads*seqs/s",
                n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True,
@@ -168,6 +210,7 @@ def main() -> int:
                            "fp32 dot products, softmax and accumulation",
                            heads_seqs_per_step=heads_seqs, seed=cf.seed),
                roofline=roofline, cpu_baseline=cpu_baseline, stages=stages, contraction=contraction,
+               all_configs=all_configs,
                host_cores=len(os.sched_getaffinity(0)), device=torch.cuda.get_device_name(0))
     print(json.dumps(out))
     return 0
