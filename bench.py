@@ -28,9 +28,10 @@ if str(ROOT) not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 
-# HBM traffic of one launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of this command (see profiles/); None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# HBM traffic of one launch of the dominant kernel (attention_rows at C4f), measured with two
+# rocprofv3 --pmc runs of `bench.py --pmc-mode` (FETCH_SIZE, then WRITE_SIZE), each scaled by what the
+# same counter reads for the 256 MiB calibration copy: profiles/bench_C4_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = 95.7e6
 PMC_COPY_BYTES = 256 << 20   # size of the calibration copy in --pmc-mode
 
 
