@@ -273,18 +273,25 @@ __device__ __forceinline__ int unit_key_score(const int *__restrict__ qu, const 
 // The keep-th largest of the values a wavefront holds in registers (NR per lane, unused slots
 // INT32_MIN): the largest T with count(v >= T) >= keep, by bisection on the value.  lo and hi are
 // wavefront-uniform; needs count(v >= lo) >= keep and hi >= every value.  Every probe is above
-// INT32_MIN, so unused slots never count.
+// INT32_MIN, so unused slots never count.  With slack > 0 the search stops at the first T whose
+// count lies in [keep, keep + slack]: still a lower bound of the keep-th largest, found sooner.
 template <int NR>
-__device__ __forceinline__ int kth_largest(const int (&v)[NR], int keep, int lo, int hi)
+__device__ __forceinline__ int kth_largest(const int (&v)[NR], int keep, int lo, int hi, int slack = 0)
 {
     lo = __builtin_amdgcn_readfirstlane(lo);
     hi = __builtin_amdgcn_readfirstlane(hi);
     while (lo < hi) {
-        const int mid = (int)(lo + ((long long)hi - lo + 1) / 2);
+        const unsigned range = (unsigned)hi - (unsigned)lo;
+        const int mid = lo + (int)((range >> 1) + (range & 1u));
         int cnt = 0;
 #pragma unroll
         for (int i = 0; i < NR; ++i) cnt += __popcll(__ballot(v[i] >= mid));
-        if (cnt >= keep) lo = mid; else hi = mid - 1;
+        if (cnt >= keep) {
+            lo = mid;
+            if (cnt <= keep + slack) break;     // slack > 0: any T with keep <= count(v >= T) <= keep + slack will do
+        } else {
+            hi = mid - 1;
+        }
     }
     return lo;
 }
@@ -438,7 +445,7 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
                 real += __popcll(__ballot(vb[i] != INT32_MIN));
             }
             int T = INT32_MIN;
-            if (real >= keep) T = kth_largest<VB>(vb, keep, wave_min(lo), wave_max(hi));
+            if (real >= keep) T = kth_largest<VB>(vb, keep, wave_min(lo), wave_max(hi), keep >> 4);
             if (lane == 0) T0s[uu] = max(T0s[uu], T);
         }
         PHASE_MARK(2);
@@ -713,37 +720,40 @@ hipError_t launch_tiles(const TilePlan &p, const dsa_shape &sh, const int8_t *Qt
 // register ring, and the maxima of tile t are taken (two scores per v_max3) while the matrix
 // core works on tile t+1.  KSPLIT wavefronts share one 64-row query tile and split the keys, so
 // that a SIMD holds several wavefronts and one's v_max3 stream fills the other's matrix-core
-// time; they combine through LDS at the end.
-// (The launch bound is at least 512 threads: with at most 256 registers per lane the compiler
-// gives the matrix core plain VGPR destinations that v_max3 can read directly.)
-template <int KSTEPS, int KSPLIT>   // k padded to 32 * KSTEPS
-__global__ __launch_bounds__(KSPLIT <= 2 ? 512 : 256 * KSPLIT) void rowmax_mfma(
+// time; they combine through LDS at the end.  A workgroup is always 8 wavefronts: 8 / KSPLIT
+// query tiles times KSPLIT key shares.
+// (With 512 threads, at most 256 registers per lane, the compiler gives the matrix core plain
+// VGPR destinations that v_max3 can read directly.)
+template <int KSTEPS, int KSPLIT, int NQ>   // k padded to 32 * KSTEPS; NQ blocks of 32 query rows per wavefront
+__global__ __launch_bounds__(512) void rowmax_mfma(
     const int8_t *__restrict__ Qt, const int8_t *__restrict__ Kt, int32_t *__restrict__ rowmax, int L, int k,
     unsigned N)
 {
-    constexpr int PD = (KSPLIT <= 2 ? 8 : 4) / KSTEPS;   // prefetch depth in tiles (KSTEPS <= 4)
-    __shared__ int part[4 * KSPLIT][64];
+    constexpr int PD = 8 / KSTEPS;                       // prefetch depth in tiles (KSTEPS <= 4)
+    constexpr int QR = 32 * NQ;                          // query rows per wavefront
+    constexpr int QSLOTS = 8 / KSPLIT;                   // query tiles per workgroup of 8 wavefronts
+    __shared__ int part[8][QR];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int col = lane & 31, half = lane >> 5;
     const int qslot = wave / KSPLIT, ks = wave % KSPLIT;
-    const unsigned qtiles_per_head = (L + 63) / 64;
-    const unsigned qtile = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + qslot;
+    const unsigned qtiles_per_head = (L + QR - 1) / QR;
+    const unsigned qtile = xcd_contiguous(blockIdx.x, gridDim.x) * QSLOTS + qslot;
     const bool live = qtile < N * qtiles_per_head;
     const unsigned n = live ? qtile / qtiles_per_head : 0;
-    const int i0 = live ? (int)(qtile % qtiles_per_head) * 64 : 0;
+    const int i0 = live ? (int)(qtile % qtiles_per_head) * QR : 0;
     const int8_t *Qh = Qt + (size_t)n * L * k, *Kh = Kt + (size_t)n * L * k;
 
     // operand piece of this lane: 16 consecutive c at 32*step + 16*half.  Beyond k (and, for
     // queries, beyond L) the query piece is zero, so the key piece there may hold anything and is
     // read from offset 0.  Key rows beyond L are read from row L-1 and masked at the end.
     int coff[KSTEPS];
-    v4i qop[2][KSTEPS];
+    v4i qop[NQ][KSTEPS];
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) {
         const int c = 32 * s + 16 * half;
         coff[s] = c < k ? c : 0;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < NQ; ++h) {
             const int qi = i0 + 32 * h + col;
             qop[h][s] = (qi < L && c < k) ? *reinterpret_cast<const v4i *>(Qh + (size_t)qi * k + c) : v4i{0, 0, 0, 0};
         }
@@ -760,24 +770,33 @@ __global__ __launch_bounds__(KSPLIT <= 2 ? 512 : 256 * KSPLIT) void rowmax_mfma(
 #pragma unroll
     for (int p = 0; p < PD; ++p) load_tile(min(ta + p, T - 1), ring[p]);
 
-    int m0 = INT32_MIN, m1 = INT32_MIN;
-    v16i pa, pb;           // scores of the previous tile, reduced while the next one is computed
+    int m[NQ];
+    v16i prev[NQ];         // scores of the previous tile, reduced while the next one is computed
 #pragma unroll
-    for (int r = 0; r < 16; ++r) pa[r] = pb[r] = INT32_MIN;
+    for (int h = 0; h < NQ; ++h) {
+        m[h] = INT32_MIN;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) prev[h][r] = INT32_MIN;
+    }
     auto step = [&](v4i (&kop)[KSTEPS]) {
-        v16i a = {0}, b = {0};
+        v16i cur[NQ];
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) {
-            a = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[s], qop[0][s], a, 0, 0, 0);
-            b = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[s], qop[1][s], b, 0, 0, 0);
+        for (int h = 0; h < NQ; ++h) {
+            cur[h] = v16i{0};
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s)
+                cur[h] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[s], qop[h][s], cur[h], 0, 0, 0);
+        }
+#ifndef DSA_ROWMAX_EXPERIMENT
+#define DSA_ROWMAX_EXPERIMENT 0     // tuning aid, never set for the library
+#endif
+#pragma unroll
+        for (int r = 0; r < (DSA_ROWMAX_EXPERIMENT == 1 ? 2 : DSA_ROWMAX_EXPERIMENT == 2 ? 8 : 16); r += 2) {
+#pragma unroll
+            for (int h = 0; h < NQ; ++h) m[h] = max(max(prev[h][r], prev[h][r + 1]), m[h]);
         }
 #pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-            m0 = max(max(pa[r], pa[r + 1]), m0);
-            m1 = max(max(pb[r], pb[r + 1]), m1);
-        }
-        pa = a;
-        pb = b;
+        for (int h = 0; h < NQ; ++h) prev[h] = cur[h];
     };
     // all tiles but the last of the sweep hold only real keys; the ring slot of tile t is (t - ta) % PD
     int t = ta;
@@ -786,33 +805,37 @@ __global__ __launch_bounds__(KSPLIT <= 2 ? 512 : 256 * KSPLIT) void rowmax_mfma(
         for (int p = 0; p < PD; ++p) {
             step(ring[p]);
             load_tile(min(t + p + PD, T - 1), ring[p]);
+            // keep the refill of slot p here, PD tiles ahead of its use: left alone, the scheduler
+            // gathers all refills at the end of the unrolled body, right before they are needed
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 #pragma unroll
     for (int p = 0; p < PD; ++p)
-        if (t + p < tb) step(ring[p]);      // the rest; pa, pb end up as tile tb-1
+        if (t + p < tb) step(ring[p]);      // the rest; prev ends up as tile tb-1
     // that tile may reach past L: register r of this lane is key row 8*(r/4) + 4*half + r%4 of it
     if (ta < tb) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             if (32 * (tb - 1) + 8 * (r / 4) + 4 * half + (r % 4) < L) {
-                m0 = max(m0, pa[r]);
-                m1 = max(m1, pb[r]);
+#pragma unroll
+                for (int h = 0; h < NQ; ++h) m[h] = max(m[h], prev[h][r]);
             }
         }
     }
-    m0 = max(m0, __shfl_xor(m0, 32, kWave));
-    m1 = max(m1, __shfl_xor(m1, 32, kWave));
-    if (half == 0) {
-        part[wave][col] = m0;
-        part[wave][32 + col] = m1;
+#pragma unroll
+    for (int h = 0; h < NQ; ++h) {
+        m[h] = max(m[h], __shfl_xor(m[h], 32, kWave));
+        if (half == 0) part[wave][32 * h + col] = m[h];
     }
     __syncthreads();
     if (ks == 0 && live) {
-        int m = part[wave][lane];
+        for (int r = lane; r < QR; r += kWave) {
+            int best = part[wave][r];
 #pragma unroll
-        for (int j = 1; j < KSPLIT; ++j) m = max(m, part[wave + j][lane]);
-        if (i0 + lane < L) rowmax[(size_t)n * L + i0 + lane] = m;
+            for (int j = 1; j < KSPLIT; ++j) best = max(best, part[wave + j][r]);
+            if (i0 + r < L) rowmax[(size_t)n * L + i0 + r] = best;
+        }
     }
 }
 
@@ -864,23 +887,34 @@ hipError_t launch_predict(const dsa_shape &sh, const int8_t *Qt, const int8_t *K
     return hipGetLastError();
 }
 
+template <int KSTEPS, int NQ>
+hipError_t launch_rowmax_q(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *rowmax, hipStream_t st)
+{
+    const unsigned N = (unsigned)sh.B * sh.H;
+    const unsigned qtiles = N * ((sh.L + 32 * NQ - 1) / (32 * NQ));
+    // enough wavefronts for a few per SIMD (1024 SIMDs), but at least 8 key tiles each
+    const int tiles = (sh.L + 31) / 32;
+    int ksplit = 1;
+    while (ksplit < 8 && (size_t)qtiles * ksplit < 2048 && tiles / (2 * ksplit) >= 8) ksplit *= 2;
+    const unsigned slots = 8 / ksplit;
+    const dim3 grid((qtiles + slots - 1) / slots), block(512);
+    switch (ksplit) {
+    case 1: hipLaunchKernelGGL((rowmax_mfma<KSTEPS, 1, NQ>), grid, block, 0, st, Qt, Kt, rowmax, sh.L, sh.k, N); break;
+    case 2: hipLaunchKernelGGL((rowmax_mfma<KSTEPS, 2, NQ>), grid, block, 0, st, Qt, Kt, rowmax, sh.L, sh.k, N); break;
+    case 4: hipLaunchKernelGGL((rowmax_mfma<KSTEPS, 4, NQ>), grid, block, 0, st, Qt, Kt, rowmax, sh.L, sh.k, N); break;
+    default: hipLaunchKernelGGL((rowmax_mfma<KSTEPS, 8, NQ>), grid, block, 0, st, Qt, Kt, rowmax, sh.L, sh.k, N); break;
+    }
+    return hipGetLastError();
+}
+
 template <int KSTEPS>
 hipError_t launch_rowmax_k(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *rowmax, hipStream_t st)
 {
-    const unsigned N = (unsigned)sh.B * sh.H;
-    const unsigned qtiles = N * ((sh.L + 63) / 64);
-    const dim3 grid((qtiles + 3) / 4);
-    // enough wavefronts for about four per SIMD (1024 SIMDs), but at least 8 key tiles each
-    const int tiles = (sh.L + 31) / 32;
-    int ksplit = 1;
-    while (ksplit < 4 && (size_t)qtiles * ksplit < 4096 && tiles / (2 * ksplit) >= 8) ksplit *= 2;
-    if (ksplit == 1)
-        hipLaunchKernelGGL((rowmax_mfma<KSTEPS, 1>), grid, dim3(256), 0, st, Qt, Kt, rowmax, sh.L, sh.k, N);
-    else if (ksplit == 2)
-        hipLaunchKernelGGL((rowmax_mfma<KSTEPS, 2>), grid, dim3(512), 0, st, Qt, Kt, rowmax, sh.L, sh.k, N);
-    else
-        hipLaunchKernelGGL((rowmax_mfma<KSTEPS, 4>), grid, dim3(1024), 0, st, Qt, Kt, rowmax, sh.L, sh.k, N);
-    return hipGetLastError();
+    // 128 query rows per wavefront (one key operand feeds four MFMAs) when that still leaves enough
+    // wavefronts to fill the chip and k is short enough for the registers; else 64
+    const size_t rows = (size_t)sh.B * sh.H * sh.L;
+    if (KSTEPS == 1 && rows >= 65536) return launch_rowmax_q<KSTEPS, 4>(sh, Qt, Kt, rowmax, st);
+    return launch_rowmax_q<KSTEPS, 2>(sh, Qt, Kt, rowmax, st);
 }
 
 hipError_t launch_rowmax(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *rowmax,
