@@ -275,7 +275,7 @@ __device__ __forceinline__ int unit_key_score(const int *__restrict__ qu, const 
 // wavefront-uniform; needs count(v >= lo) >= keep and hi >= every value.  Every probe is above
 // INT32_MIN, so unused slots never count.  With slack > 0 the search stops at the first T whose
 // count lies in [keep, keep + slack]: still a lower bound of the keep-th largest, found sooner.
-template <int NR>
+template <int NR, int USED = NR>
 __device__ __forceinline__ int kth_largest(const int (&v)[NR], int keep, int lo, int hi, int slack = 0)
 {
     lo = __builtin_amdgcn_readfirstlane(lo);
@@ -285,7 +285,7 @@ __device__ __forceinline__ int kth_largest(const int (&v)[NR], int keep, int lo,
         const int mid = lo + (int)((range >> 1) + (range & 1u));
         int cnt = 0;
 #pragma unroll
-        for (int i = 0; i < NR; ++i) cnt += __popcll(__ballot(v[i] >= mid));
+        for (int i = 0; i < USED; ++i) cnt += __popcll(__ballot(v[i] >= mid));
         if (cnt >= keep) {
             lo = mid;
             if (cnt <= keep + slack) break;     // slack > 0: any T with keep <= count(v >= T) <= keep + slack will do
@@ -294,6 +294,21 @@ __device__ __forceinline__ int kth_largest(const int (&v)[NR], int keep, int lo,
         }
     }
     return lo;
+}
+
+// kth_largest over the first `used` (wavefront-uniform) registers only.
+template <int NR>
+__device__ __forceinline__ int kth_largest_of(const int (&v)[NR], int used, int keep, int lo, int hi, int slack = 0)
+{
+    switch (used) {
+    case 1: return kth_largest<NR, 1>(v, keep, lo, hi, slack);
+    case 2: return kth_largest<NR, (NR >= 2 ? 2 : NR)>(v, keep, lo, hi, slack);
+    case 3: return kth_largest<NR, (NR >= 3 ? 3 : NR)>(v, keep, lo, hi, slack);
+    case 4: return kth_largest<NR, (NR >= 4 ? 4 : NR)>(v, keep, lo, hi, slack);
+    case 5: return kth_largest<NR, (NR >= 5 ? 5 : NR)>(v, keep, lo, hi, slack);
+    case 6: return kth_largest<NR, (NR >= 6 ? 6 : NR)>(v, keep, lo, hi, slack);
+    default: return kth_largest<NR>(v, keep, lo, hi, slack);
+    }
 }
 
 // (A) for one wavefront and one chunk: scores of TC tiles into registers plus bucket maxima.
@@ -445,7 +460,7 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
                 real += __popcll(__ballot(vb[i] != INT32_MIN));
             }
             int T = INT32_MIN;
-            if (real >= keep) T = kth_largest<VB>(vb, keep, wave_min(lo), wave_max(hi), keep >> 4);
+            if (real >= keep) T = kth_largest_of<VB>(vb, (NBT + kWave - 1) / kWave, keep, wave_min(lo), wave_max(hi), keep >> 4);
             if (lane == 0) T0s[uu] = max(T0s[uu], T);
         }
         PHASE_MARK(2);
@@ -565,7 +580,7 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
             }
             PHASE_MARK(7);
             // every candidate reaches T0 and there are at least keep of them
-            const int T = kth_largest<NR>(sc, keep, T0, wave_max(hi));
+            const int T = kth_largest_of<NR>(sc, groups, keep, T0, wave_max(hi));
             PHASE_MARK(8);
             int gt = 0;
 #pragma unroll
