@@ -16,47 +16,96 @@ namespace {
 constexpr int kRowWaves = 4;          // query rows (wavefronts) per workgroup
 constexpr int kMaxKeep = 8192;        // scores of a row in LDS: 4 waves * 8192 * 4 B = 128 KB
 
-template <typename T> struct Piece;   // 16 bytes of a row as floats
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// 16 bytes of a row: how to load them, to take a dot product of two of them and to add p times one
+// of them to fp32 accumulators.
+template <typename T> struct Piece;
 template <> struct Piece<float> {
     static constexpr int N = 4;
-    static __device__ __forceinline__ void load(const float *p, float (&v)[4])
+    typedef float4 raw_t;
+    static __device__ __forceinline__ raw_t load(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+    static __device__ __forceinline__ float dot(raw_t a, raw_t b)
     {
-        const float4 x = *reinterpret_cast<const float4 *>(p);
-        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+        return fmaf(a.w, b.w, fmaf(a.z, b.z, fmaf(a.y, b.y, a.x * b.x)));
+    }
+    static __device__ __forceinline__ void axpy(float (&o)[4], float p, raw_t b)
+    {
+        o[0] = fmaf(p, b.x, o[0]); o[1] = fmaf(p, b.y, o[1]); o[2] = fmaf(p, b.z, o[2]); o[3] = fmaf(p, b.w, o[3]);
     }
 };
-template <> struct Piece<uint16_t> {  // bfloat16: the upper half of a float
+// bfloat16: v_dot2_f32_bf16 multiplies two packed pairs and accumulates in fp32, so no element is
+// ever unpacked.  For the weighted sum the weight is rounded to bfloat16 (relative 2^-9, inside the
+// 2e-2 budget of bfloat16 inputs) and paired with a zero: (v0, v1) . (p, 0) = p v0, (v0, v1) . (0, p) = p v1.
+template <> struct Piece<uint16_t> {
     static constexpr int N = 8;
-    static __device__ __forceinline__ void load(const uint16_t *p, float (&v)[8])
+    typedef uint4 raw_t;
+    static __device__ __forceinline__ raw_t load(const uint16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
+    static __device__ __forceinline__ float dot2(unsigned a, unsigned b, float acc)
     {
-        const uint4 x = *reinterpret_cast<const uint4 *>(p);
-        const unsigned w[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[2 * i] = __uint_as_float(w[i] << 16);
-            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-        }
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), acc, false);
+    }
+    static __device__ __forceinline__ float dot(raw_t a, raw_t b)
+    {
+        return dot2(a.w, b.w, dot2(a.z, b.z, dot2(a.y, b.y, dot2(a.x, b.x, 0.f))));
+    }
+    static __device__ __forceinline__ void axpy(float (&o)[8], float p, raw_t b)
+    {
+        const unsigned lo = __builtin_bit_cast(unsigned short, (__bf16)p), hi = lo << 16;
+        o[0] = dot2(b.x, lo, o[0]); o[1] = dot2(b.x, hi, o[1]);
+        o[2] = dot2(b.y, lo, o[2]); o[3] = dot2(b.y, hi, o[3]);
+        o[4] = dot2(b.z, lo, o[4]); o[5] = dot2(b.z, hi, o[5]);
+        o[6] = dot2(b.w, lo, o[6]); o[7] = dot2(b.w, hi, o[7]);
     }
 };
 
-// Sum over the LPR lanes that hold one row (LPR is a power of two <= 32).
+// Cross-lane moves inside a row of 16 lanes without LDS traffic (DPP).
+template <int CTRL> __device__ __forceinline__ float dpp_f(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+}
+// Sum over the LPR neighbouring lanes that hold one row (LPR = 8, 16 or 32); every one of them gets it.
 template <int LPR> __device__ __forceinline__ float piece_sum(float x)
 {
-#pragma unroll
-    for (int off = 1; off < LPR; off <<= 1) x += __shfl_xor(x, off, kWave);
+    x += dpp_f<0xB1>(x);                          // lane ^ 1 (quad permute 1,0,3,2)
+    x += dpp_f<0x4E>(x);                          // lane ^ 2 (quad permute 2,3,0,1)
+    x += dpp_f<0x141>(x);                         // the other quad of the 8 (half-row mirror)
+    if (LPR >= 16) x += dpp_f<0x140>(x);          // the other half of the 16 (row mirror)
+    if (LPR >= 32) x += __shfl_xor(x, 16, kWave);
     return x;
 }
-// Combine the 64/LPR row groups of a wavefront.
+// Combine the 64/LPR row groups of a wavefront: lane (group, piece) with every (group', piece).
 template <int LPR> __device__ __forceinline__ float groups_sum(float x)
 {
+    if (LPR <= 8) x += dpp_f<0x128>(x);           // lane ^ 8 (row rotate by 8)
 #pragma unroll
-    for (int off = LPR; off < kWave; off <<= 1) x += __shfl_xor(x, off, kWave);
+    for (int off = (LPR <= 8 ? 16 : LPR); off < kWave; off <<= 1) x += __shfl_xor(x, off, kWave);
     return x;
 }
 template <int LPR> __device__ __forceinline__ float groups_max(float x)
 {
+    if (LPR <= 8) x = fmaxf(x, dpp_f<0x128>(x));
 #pragma unroll
-    for (int off = LPR; off < kWave; off <<= 1) x = fmaxf(x, __shfl_xor(x, off, kWave));
+    for (int off = (LPR <= 8 ? 16 : LPR); off < kWave; off <<= 1) x = fmaxf(x, __shfl_xor(x, off, kWave));
+    return x;
+}
+
+// Reductions over all 64 lanes.
+__device__ __forceinline__ float wave_all_sum(float x)
+{
+    x = piece_sum<16>(x);
+    x += __shfl_xor(x, 16, kWave);
+    x += __shfl_xor(x, 32, kWave);
+    return x;
+}
+__device__ __forceinline__ float wave_all_max(float x)
+{
+    x = fmaxf(x, dpp_f<0xB1>(x));
+    x = fmaxf(x, dpp_f<0x4E>(x));
+    x = fmaxf(x, dpp_f<0x141>(x));
+    x = fmaxf(x, dpp_f<0x140>(x));
+    x = fmaxf(x, __shfl_xor(x, 16, kWave));
+    x = fmaxf(x, __shfl_xor(x, 32, kWave));
     return x;
 }
 
@@ -67,15 +116,17 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
     const int32_t *__restrict__ idx, const float *__restrict__ Pin, float *__restrict__ S,
     float *__restrict__ O, int L, int keep, int vec, float scale, unsigned total_rows)
 {
-    constexpr int E = Piece<T>::N;        // elements per lane
+    typedef Piece<T> P;
+    constexpr int E = P::N;               // elements per lane
     constexpr int LPR = D / E;            // lanes per row
     constexpr int RPI = kWave / LPR;      // gathered rows per wavefront instruction
     extern __shared__ float lds_scores[];
 
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int sub = lane % LPR, grp = lane / LPR;
     const unsigned vblock = xcd_contiguous(blockIdx.x, gridDim.x);
-    const unsigned row = vblock * kRowWaves + wave;
+    const unsigned row = vblock * kRowWaves + wave;                 // wavefront-uniform from here on
     const bool live = row < total_rows;
     const unsigned r = live ? row : total_rows - 1;      // dead waves shadow a real row, write nothing
     const unsigned n = r / (unsigned)L, i = r % (unsigned)L;
@@ -84,21 +135,14 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
 
     float m = -INFINITY;
     if (MODE != kSpmm) {
-        float q[E];
-        Piece<T>::load(Q + (size_t)r * D + sub * E, q);
-#pragma unroll
-        for (int e = 0; e < E; ++e) q[e] *= scale;
-        const T *Kh = K + (size_t)n * L * D + sub * E;
+        const typename P::raw_t q = P::load(Q + (size_t)r * D + sub * E);
+        const T *Kh = K + (size_t)n * L * D;
         for (int t0 = 0; t0 < keep; t0 += RPI) {
             const int t = t0 + grp;
             const bool valid = t < keep;
             const int j = min(max(list[valid ? t : keep - 1], 0), L - 1);   // stay inside K for any idx
-            float kv[E];
-            Piece<T>::load(Kh + (size_t)j * D, kv);
-            float acc = 0.f;
-#pragma unroll
-            for (int e = 0; e < E; ++e) acc = fmaf(q[e], kv[e], acc);
-            acc = piece_sum<LPR>(acc);
+            const typename P::raw_t kv = P::load(Kh + (unsigned)(j * D + sub * E));
+            const float acc = piece_sum<LPR>(P::dot(q, kv)) * scale;
             if (valid) {
                 m = fmaxf(m, acc);
                 if (sub == 0) {
@@ -115,7 +159,7 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
     float o[E], z = 0.f;
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] = 0.f;
-    const T *Vh = V + (size_t)n * L * D + sub * E;
+    const T *Vh = V + (size_t)n * L * D;
     for (int t0 = 0; t0 < keep; t0 += RPI) {
         const int t = t0 + grp;
         const bool valid = t < keep;
@@ -125,11 +169,9 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
         if (MODE == kSpmm) p = Pin[(size_t)r * keep + tt];
         else p = __expf(sc[tt] - m);
         p = valid ? p : 0.f;
-        float vv[E];
-        Piece<T>::load(Vh + (size_t)j * D, vv);
+        const typename P::raw_t vv = P::load(Vh + (unsigned)(j * D + sub * E));
         z += p;
-#pragma unroll
-        for (int e = 0; e < E; ++e) o[e] = fmaf(p, vv[e], o[e]);
+        P::axpy(o, p, vv);
     }
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] = groups_sum<LPR>(o[e]);
@@ -299,10 +341,10 @@ __global__ __launch_bounds__(kRowWaves *kWave) void softmax_rows(const float *S,
     float *p = P + (size_t)row * keep;
     float m = -INFINITY;
     for (int t = lane; t < keep; t += kWave) m = fmaxf(m, s[t]);
-    m = groups_max<1>(m);
+    m = wave_all_max(m);
     float z = 0.f;
     for (int t = lane; t < keep; t += kWave) z += __expf(s[t] - m);
-    z = groups_sum<1>(z);
+    z = wave_all_sum(z);
     const float inv = 1.f / z;
     for (int t = lane; t < keep; t += kWave) p[t] = __expf(s[t] - m) * inv;
 }
