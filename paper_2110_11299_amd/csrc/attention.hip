@@ -14,7 +14,7 @@ namespace dsa {
 namespace {
 
 constexpr int kRowWaves = 4;          // query rows (wavefronts) per workgroup
-constexpr int kMaxKeep = 8192;        // scores of a row in LDS: 4 waves * 8192 * 4 B = 128 KB
+constexpr int kMaxKeep = 4096;        // list and scores of a row in LDS: 4 waves * 4096 * 8 B = 128 KB
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
@@ -131,23 +131,35 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
     const unsigned r = live ? row : total_rows - 1;      // dead waves shadow a real row, write nothing
     const unsigned n = r / (unsigned)L, i = r % (unsigned)L;
     const int32_t *list = idx + ((size_t)n * (L / vec) + i / vec) * keep;
-    float *sc = lds_scores + wave * keep;
+    // per wavefront in LDS: the row's key list (clamped into [0, L), so that no idx can send a
+    // gather outside K / V) and, in the fused mode, its scores
+    int *sl = reinterpret_cast<int *>(lds_scores) + wave * (MODE == kFused ? 2 : 1) * keep;
+    float *sc = reinterpret_cast<float *>(sl + keep);
+    for (int t = lane; t < keep; t += kWave) sl[t] = min(max(list[t], 0), L - 1);
+    __syncthreads();
+    constexpr int U = 4;                  // independent gathers in flight per lane
 
     float m = -INFINITY;
     if (MODE != kSpmm) {
         const typename P::raw_t q = P::load(Q + (size_t)r * D + sub * E);
         const T *Kh = K + (size_t)n * L * D;
-        for (int t0 = 0; t0 < keep; t0 += RPI) {
-            const int t = t0 + grp;
-            const bool valid = t < keep;
-            const int j = min(max(list[valid ? t : keep - 1], 0), L - 1);   // stay inside K for any idx
-            const typename P::raw_t kv = P::load(Kh + (unsigned)(j * D + sub * E));
-            const float acc = piece_sum<LPR>(P::dot(q, kv)) * scale;
-            if (valid) {
-                m = fmaxf(m, acc);
-                if (sub == 0) {
-                    if (MODE == kSddmm) { if (live) S[(size_t)r * keep + t] = acc; }
-                    else sc[t] = acc;
+        for (int t0 = 0; t0 < keep; t0 += U * RPI) {
+            typename P::raw_t kv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int j = sl[min(t0 + u * RPI + grp, keep - 1)];
+                kv[u] = P::load(Kh + (unsigned)(j * D + sub * E));
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int t = t0 + u * RPI + grp;
+                const float acc = piece_sum<LPR>(P::dot(q, kv[u])) * scale;
+                if (t < keep) {
+                    m = fmaxf(m, acc);
+                    if (sub == 0) {
+                        if (MODE == kSddmm) { if (live) S[(size_t)r * keep + t] = acc; }
+                        else sc[t] = acc;
+                    }
                 }
             }
         }
@@ -160,18 +172,23 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] = 0.f;
     const T *Vh = V + (size_t)n * L * D;
-    for (int t0 = 0; t0 < keep; t0 += RPI) {
-        const int t = t0 + grp;
-        const bool valid = t < keep;
-        const int tt = valid ? t : keep - 1;
-        const int j = min(max(list[tt], 0), L - 1);
-        float p;
-        if (MODE == kSpmm) p = Pin[(size_t)r * keep + tt];
-        else p = __expf(sc[tt] - m);
-        p = valid ? p : 0.f;
-        const typename P::raw_t vv = P::load(Vh + (unsigned)(j * D + sub * E));
-        z += p;
-        P::axpy(o, p, vv);
+    for (int t0 = 0; t0 < keep; t0 += U * RPI) {
+        typename P::raw_t vv[U];
+        float p[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u * RPI + grp;
+            const int tt = min(t, keep - 1);
+            vv[u] = P::load(Vh + (unsigned)(sl[tt] * D + sub * E));
+            if (MODE == kSpmm) p[u] = Pin[(size_t)r * keep + tt];
+            else p[u] = __expf(sc[tt] - m);
+            p[u] = t < keep ? p[u] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            z += p[u];
+            P::axpy(o, p[u], vv[u]);
+        }
     }
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] = groups_sum<LPR>(o[e]);
@@ -355,7 +372,8 @@ hipError_t launch_rows(AttnMode mode, const dsa_shape &sh, const void *Q, const 
 {
     const unsigned rows = (unsigned)sh.B * sh.H * sh.L;
     const dim3 grid((rows + kRowWaves - 1) / kRowWaves), block(kRowWaves * kWave);
-    const size_t lds = mode == kFused ? (size_t)kRowWaves * sh.keep * sizeof(float) : 0;
+    // per wavefront: the key list, plus the scores in the fused mode
+    const size_t lds = (size_t)kRowWaves * sh.keep * sizeof(float) * (mode == kFused ? 2 : 1);
     const T *q = static_cast<const T *>(Q), *k = static_cast<const T *>(K), *v = static_cast<const T *>(V);
     if (mode == kFused) {
         auto kern = attention_rows<T, D, kFused>;
@@ -367,11 +385,23 @@ hipError_t launch_rows(AttnMode mode, const dsa_shape &sh, const void *Q, const 
         hipLaunchKernelGGL(kern, grid, block, lds, st, q, k, v, idx, Pin, S, O, sh.L, sh.keep, sh.vec,
                            sh.scale, rows);
     } else if (mode == kSddmm) {
-        hipLaunchKernelGGL((attention_rows<T, D, kSddmm>), grid, block, 0, st, q, k, v, idx, Pin, S, O,
-                           sh.L, sh.keep, sh.vec, sh.scale, rows);
+        auto kern = attention_rows<T, D, kSddmm>;
+        if (lds > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(kern, grid, block, lds, st, q, k, v, idx, Pin, S, O, sh.L, sh.keep, sh.vec, sh.scale,
+                           rows);
     } else {
-        hipLaunchKernelGGL((attention_rows<T, D, kSpmm>), grid, block, 0, st, q, k, v, idx, Pin, S, O,
-                           sh.L, sh.keep, sh.vec, sh.scale, rows);
+        auto kern = attention_rows<T, D, kSpmm>;
+        if (lds > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(kern, grid, block, lds, st, q, k, v, idx, Pin, S, O, sh.L, sh.keep, sh.vec, sh.scale,
+                           rows);
     }
     return hipGetLastError();
 }
