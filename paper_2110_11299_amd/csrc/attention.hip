@@ -13,7 +13,10 @@
 namespace dsa {
 namespace {
 
-constexpr int kRowWaves = 4;          // query rows (wavefronts) per workgroup
+#ifndef DSA_ROW_WAVES
+#define DSA_ROW_WAVES 4
+#endif
+constexpr int kRowWaves = DSA_ROW_WAVES;   // query rows (wavefronts) per workgroup
 constexpr int kMaxKeep = 4096;        // list and scores of a row in LDS: 4 waves * 4096 * 8 B = 128 KB
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -137,7 +140,10 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
     float *sc = reinterpret_cast<float *>(sl + keep);
     for (int t = lane; t < keep; t += kWave) sl[t] = min(max(list[t], 0), L - 1);
     __syncthreads();
-    constexpr int U = 4;                  // independent gathers in flight per lane
+#ifndef DSA_ATTN_U
+#define DSA_ATTN_U 4
+#endif
+    constexpr int U = DSA_ATTN_U;         // independent gathers in flight per lane
 
     float m = -INFINITY;
     if (MODE != kSpmm) {

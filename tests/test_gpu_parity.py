@@ -111,6 +111,12 @@ EDGE = [
     dict(B=1, H=1, L=1, d=64, dtype="f32", k=16, vec=1, keep=1),
     dict(B=1, H=1, L=520, d=64, dtype="f32", k=32, vec=1, keep=519),
     dict(B=1, H=1, L=2304, d=64, dtype="bf16", k=32, vec=1, keep=1200, n_global=5),
+    # several key chunks per workgroup, fine-grained and vector-wise; long contraction (8 * 80)
+    dict(B=1, H=2, L=6000, d=64, dtype="bf16", k=32, vec=1, keep=60, n_global=7),
+    dict(B=1, H=1, L=20000, d=64, dtype="bf16", k=16, vec=8, keep=100, n_global=9),
+    dict(B=1, H=1, L=12288, d=128, dtype="bf16", k=64, vec=8, keep=600),
+    dict(B=2, H=1, L=328, d=64, dtype="f32", k=80, vec=8, keep=33),
+    dict(B=1, H=1, L=3000, d=64, dtype="f32", k=112, vec=1, keep=300),
 ]
 
 
@@ -134,6 +140,41 @@ def test_mask_with_heavy_ties(dsa, oracle, vec, lo, hi):
         idx = dsa.dsa_predict_mask(sh, torch.from_numpy(Qt).cuda(), torch.from_numpy(Kt).cuda())
         want = oracle.predict_mask(Qt, Kt, keep, vec)
         assert np.array_equal(idx.cpu().numpy().reshape(want.shape), want)
+
+
+def test_reproducible_and_stream_ordered(dsa, oracle, workload):
+    """Same inputs, same bits; and the path runs on whatever stream the caller makes current."""
+    import torch
+    x = workload("C3")
+    cfg, dev = x.cfg, to_dev(x)
+    sh = shape_of(dsa, cfg)
+    O1, idx1 = dsa.dsa_attention_fwd(sh, dev["Q"], dev["K"], dev["V"], dev["Qt"], dev["Kt"])
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        O2, idx2 = dsa.dsa_attention_fwd(sh, dev["Q"], dev["K"], dev["V"], dev["Qt"], dev["Kt"])
+    side.synchronize()
+    assert torch.equal(idx1, idx2) and torch.equal(O1, O2)
+    x = workload("C2")
+    cfg, dev = x.cfg, to_dev(x)
+    sh = shape_of(dsa, cfg)
+    a = dsa.dsa_attention_fwd(sh, dev["Q"], dev["K"], dev["V"], dev["Qt"], dev["Kt"])
+    b = dsa.dsa_attention_fwd(sh, dev["Q"], dev["K"], dev["V"], dev["Qt"], dev["Kt"])
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_invalid_indices_cannot_leave_the_tensors(dsa):
+    """The attention entry points clamp whatever idx holds into [0, L): garbage in, no fault."""
+    import torch
+    B, H, L, d, keep = 1, 2, 128, 64, 9
+    sh = dsa.make_shape(B, H, L, d, 16, keep, 1, dsa.DSA_F32, 0.125)
+    Q = torch.randn((B, H, L, d), device="cuda")
+    idx = torch.full((B, H, L, keep), 2_000_000_000, dtype=torch.int32, device="cuda")
+    idx[..., ::2] = -5
+    O = dsa.dsa_masked_attention(sh, Q, Q, Q, idx)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(O).all())
 
 
 def test_outputs_stay_inside_their_buffers(dsa, oracle, workload):
