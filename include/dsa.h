@@ -64,10 +64,10 @@ typedef enum { DSA_F32 = 0, DSA_BF16 = 1 } dsa_dtype;
  * section 4.2 for keep; section 5.1 for vec). */
 typedef struct {
     int32_t B, H;   /* batch, heads: B*H independent problems, each >= 1                      */
-    int32_t L;      /* sequence length, 1 <= L <= 65536, L % vec == 0                         */
+    int32_t L;      /* sequence length, 1 <= L <= 32768 for the predictor, L % vec == 0       */
     int32_t d;      /* head dimension of Q, K, V: 64 or 128                                   */
     int32_t k;      /* projection dimension of Qt, Kt: a multiple of 16, 16 <= k <= 128       */
-    int32_t keep;   /* kept keys per selection unit, 1 <= keep <= L                           */
+    int32_t keep;   /* kept keys per selection unit, 1 <= keep <= L (attention: <= 4096)      */
     int32_t vec;    /* mask granularity in query rows: 1 (fine-grained) or 8 (vector-wise)    */
     int32_t dtype;  /* dsa_dtype of Q, K, V                                                   */
     float scale;    /* factor on the exact scores before softmax; 1/sqrt(d) in equation 2     */
@@ -115,6 +115,13 @@ dsa_status dsa_attention_fwd(const dsa_shape *shape, const void *Q, const void *
  * rowmax[b,h,i] = max_j S~[b,h,i,j] (int32 [B,H,L]).  Uses B, H, L, k of the shape only. */
 dsa_status dsa_approx_rowmax(const dsa_shape *shape, const int8_t *Qt, const int8_t *Kt,
                              int32_t *rowmax, void *stream);
+
+/* Measurement aid for step (a): runs `blocks` workgroups of 4 wavefronts, each issuing 4*iters
+ * independent int8 MFMAs (32x32x32) with no memory traffic, i.e. 4*blocks*4*iters*65536 int8
+ * operations in all.  Timing it gives the matrix-core rate the chip sustains at its own clocks,
+ * to set beside the published peak when judging dsa_approx_rowmax.  `sink` (int32 [blocks*256],
+ * device) receives values of no meaning. */
+dsa_status dsa_mfma_i8_sustained(int32_t blocks, int32_t iters, int32_t *sink, void *stream);
 
 const char *dsa_status_string(dsa_status status);
 

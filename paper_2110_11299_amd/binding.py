@@ -18,8 +18,8 @@ DSA_F32, DSA_BF16 = 0, 1
 
 EXPORTS = [
     "dsa_keep_from_ratio", "dsa_workspace_bytes", "dsa_predict_mask", "dsa_sddmm", "dsa_sparse_softmax",
-    "dsa_spmm", "dsa_masked_attention", "dsa_attention_fwd", "dsa_approx_rowmax", "dsa_status_string",
-    "dsa_version",
+    "dsa_spmm", "dsa_masked_attention", "dsa_attention_fwd", "dsa_approx_rowmax", "dsa_mfma_i8_sustained",
+    "dsa_status_string", "dsa_version",
 ]
 
 
@@ -67,6 +67,8 @@ def lib():
         L.dsa_attention_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dsa_approx_rowmax.restype = i32
         L.dsa_approx_rowmax.argtypes = [shp, vp, vp, vp, vp]
+        L.dsa_mfma_i8_sustained.restype = i32
+        L.dsa_mfma_i8_sustained.argtypes = [i32, i32, vp, vp]
         L.dsa_status_string.restype = ctypes.c_char_p
         L.dsa_status_string.argtypes = [i32]
         L.dsa_version.restype = ctypes.c_char_p
@@ -210,3 +212,13 @@ def dsa_approx_rowmax(shape, Qt, Kt, rowmax=None):
     _check(lib().dsa_approx_rowmax(ctypes.byref(shape), _ptr(Qt), _ptr(Kt), _ptr(rowmax), _stream()),
            "dsa_approx_rowmax")
     return rowmax
+
+
+def dsa_mfma_i8_sustained(blocks: int, iters: int, sink=None):
+    """Launches the pure int8 MFMA stream; returns the number of int8 operations it performs."""
+    import torch
+    if sink is None:
+        sink = torch.empty(blocks * 256, dtype=torch.int32, device="cuda")
+    _dev(sink, torch.int32, (blocks * 256,))
+    _check(lib().dsa_mfma_i8_sustained(blocks, iters, _ptr(sink), _stream()), "dsa_mfma_i8_sustained")
+    return 4 * blocks * 4 * iters * 65536

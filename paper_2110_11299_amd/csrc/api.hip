@@ -150,6 +150,14 @@ dsa_status dsa_approx_rowmax(const dsa_shape *sh, const int8_t *Qt, const int8_t
     return from_hip(dsa::launch_rowmax(*sh, Qt, Kt, rowmax, (hipStream_t)stream));
 }
 
+dsa_status dsa_mfma_i8_sustained(int32_t blocks, int32_t iters, int32_t *sink, void *stream)
+{
+    if (!sink) return DSA_ERR_NULL;
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return DSA_ERR_SHAPE;
+    if (!aligned16(sink)) return DSA_ERR_ALIGN;
+    return from_hip(dsa::launch_mfma_i8_stream(blocks, iters, sink, (hipStream_t)stream));
+}
+
 const char *dsa_status_string(dsa_status s)
 {
     switch (s) {

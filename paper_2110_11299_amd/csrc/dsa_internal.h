@@ -34,6 +34,8 @@ hipError_t launch_softmax(const dsa_shape &sh, const float *S, float *P, hipStre
 hipError_t launch_rowmax(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *rowmax,
                          hipStream_t st);
 
+hipError_t launch_mfma_i8_stream(int blocks, int iters, int32_t *sink, hipStream_t st);
+
 // Largest `keep` the attention kernels accept (scores of one row are staged in LDS).
 int attention_max_keep();
 // Largest L the predict kernel accepts.

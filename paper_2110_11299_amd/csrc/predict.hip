@@ -902,6 +902,24 @@ hipError_t launch_predict(const dsa_shape &sh, const int8_t *Qt, const int8_t *K
     return hipGetLastError();
 }
 
+// Nothing but v_mfma_i32_32x32x32_i8: four independent accumulation chains per wavefront, no memory
+// traffic inside the loop.  Measures the int8 matrix-core rate the chip sustains at its own clocks,
+// the yardstick for rowmax_mfma next to the published peak.
+__global__ __launch_bounds__(256) void mfma_i8_stream(int iters, int32_t *__restrict__ sink)
+{
+    v4i a, b;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { a[i] = 0x01020304 * (i + 1) + (int)threadIdx.x; b[i] = 0x04030201 * (i + 1) - (int)threadIdx.x; }
+    v16i c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+    for (int i = 0; i < iters; ++i) {
+        c0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c3, 0, 0, 0);
+    }
+    sink[blockIdx.x * 256 + threadIdx.x] = c0[0] + c1[1] + c2[2] + c3[3];
+}
+
 template <int KSTEPS, int NQ>
 hipError_t launch_rowmax_q(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *rowmax, hipStream_t st)
 {
@@ -928,7 +946,7 @@ hipError_t launch_rowmax_k(const dsa_shape &sh, const int8_t *Qt, const int8_t *
     // 128 query rows per wavefront (one key operand feeds four MFMAs) when that still leaves enough
     // wavefronts to fill the chip and k is short enough for the registers; else 64
     const size_t rows = (size_t)sh.B * sh.H * sh.L;
-    if (KSTEPS == 1 && rows >= 65536) return launch_rowmax_q<KSTEPS, 4>(sh, Qt, Kt, rowmax, st);
+    if (KSTEPS <= 2 && rows >= 65536) return launch_rowmax_q<KSTEPS, 4>(sh, Qt, Kt, rowmax, st);
     return launch_rowmax_q<KSTEPS, 2>(sh, Qt, Kt, rowmax, st);
 }
 
@@ -941,6 +959,12 @@ hipError_t launch_rowmax(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt
     case 3: return launch_rowmax_k<3>(sh, Qt, Kt, rowmax, st);
     default: return launch_rowmax_k<4>(sh, Qt, Kt, rowmax, st);
     }
+}
+
+hipError_t launch_mfma_i8_stream(int blocks, int iters, int32_t *sink, hipStream_t st)
+{
+    hipLaunchKernelGGL(mfma_i8_stream, dim3(blocks), dim3(256), 0, st, iters, sink);
+    return hipGetLastError();
 }
 
 }  // namespace dsa
