@@ -116,6 +116,18 @@ dsa_status dsa_attention_fwd(const dsa_shape *shape, const void *Q, const void *
 dsa_status dsa_approx_rowmax(const dsa_shape *shape, const int8_t *Qt, const int8_t *Kt,
                              int32_t *rowmax, void *stream);
 
+/* The step in front of (a) (section 3.1, equation 5: the reduced-dimension, low-precision
+ * projections), for one tensor X [B,H,L,d] (Q or K; dtype as in the shape) and one projection
+ * matrix R [d,k] (float, row-major, device):
+ *     Y[r,j] = sum_c X[r,c] R[c,j]   in fp32, as one chain of fused multiply-adds in increasing c,
+ *     amax = max |Y| over the whole tensor,  s = 127 / amax  (fp32 division),
+ *     Xt[r,j] = clip(rint(Y[r,j] * s), -127, 127)   (rint: halves to even; all zero if amax = 0),
+ * so the int8 codes are reproducible bit for bit.  Xt is int8 [B,H,L,k]; amax_out (nullable, device
+ * float) receives amax; `ws` is device scratch of at least dsa_project_workspace_bytes(). */
+size_t dsa_project_workspace_bytes(const dsa_shape *shape);
+dsa_status dsa_project_quantize(const dsa_shape *shape, const void *X, const float *R, int8_t *Xt,
+                                float *amax_out, void *ws, size_t ws_bytes, void *stream);
+
 /* Measurement aid for step (a): runs `blocks` workgroups of 4 wavefronts, each issuing 4*iters
  * independent int8 MFMAs (32x32x32) with no memory traffic, i.e. 4*blocks*4*iters*65536 int8
  * operations in all.  Timing it gives the matrix-core rate the chip sustains at its own clocks,

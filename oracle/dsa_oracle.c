@@ -24,7 +24,14 @@
  *           (equation 4: masked entries get -c and so weight 0 -> softmax over kept only).
  *   step 6  O[i,:] = sum_t P[i,t] V[j_t,:]            (equation 3: the SpMM).
  *
- * Floating point is double throughout; Q, K, V arrive as float (bfloat16 inputs are
+ *   step 0  (the step in front of the path, section 3.1 equation 5: reduced-dimension, low-precision
+ *           projections)  Y = X R,  Q~ = quantise(Y) symmetric per tensor to int8.  The paper
+ *           fixes neither the precision of the projection nor the quantiser; because a rounding
+ *           decides an integer code here, this step alone is evaluated in the kernel's precision:
+ *           fp32, one chain of fused multiply-adds in increasing c, fp32 scale 127/max|Y|, round
+ *           half to even.
+ *
+ * Floating point is double throughout the attention path; Q, K, V arrive as float (bfloat16 inputs are
  * widened exactly by the caller).  Every function can be restricted to a list of units
  * / rows so that full-size workloads can be spot-checked.
  *
@@ -232,4 +239,35 @@ int32_t dsao_masked_attention(const float *Q, const float *K, const float *V, co
     if (!S_out) free(S);
     if (!P_out) free(P);
     return rc;
+}
+
+/* Step 0: Xt [rows, k] = quantise(X [rows, d] . R [d, k]); *amax = max |Y|.  fp32 by design (see
+ * the header comment): y is built by fmaf in increasing c, exactly one rounding per term. */
+int32_t dsao_project_quantize(const float *X, const float *R, int64_t rows, int32_t d, int32_t k,
+                              int8_t *Xt, float *amax_out)
+{
+    if (!X || !R || !Xt || rows < 0 || d < 1 || k < 1) return 1;
+    float *Y = (float *)malloc(sizeof(float) * (size_t)rows * (size_t)k + 4);
+    if (!Y) return 1;
+    float amax = 0.0f;
+#pragma omp parallel for schedule(static) reduction(max : amax)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int32_t j = 0; j < k; ++j) {
+            float y = 0.0f;
+            for (int32_t c = 0; c < d; ++c) y = fmaf(X[r * d + c], R[(int64_t)c * k + j], y);
+            Y[r * k + j] = y;
+            if (fabsf(y) > amax) amax = fabsf(y);
+        }
+    }
+    const float s = amax > 0.0f ? 127.0f / amax : 0.0f;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < rows * (int64_t)k; ++t) {
+        float v = rintf(Y[t] * s);            /* default rounding mode: halves to even */
+        if (v > 127.0f) v = 127.0f;
+        if (v < -127.0f) v = -127.0f;
+        Xt[t] = (int8_t)v;
+    }
+    if (amax_out) *amax_out = amax;
+    free(Y);
+    return 0;
 }

@@ -53,6 +53,8 @@ def _load():
         lib.dsao_masked_attention.restype = i32
         lib.dsao_masked_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, f64,
                                               vp, i64, vp, vp, vp]
+        lib.dsao_project_quantize.restype = i32
+        lib.dsao_project_quantize.argtypes = [vp, vp, i64, i32, i32, vp, vp]
         _lib = lib
     return _lib
 
@@ -198,3 +200,20 @@ def attention_fwd(Q, K, V, Qt, Kt, keep, scale, vec=1):
     """Whole path, all rows.  Returns (O float64 [N*L, d], idx int32 [N*L/vec, keep])."""
     idx = predict_mask(Qt, Kt, keep, vec)
     return masked_attention(Q, K, V, idx, scale, vec), idx
+
+
+def project_quantize(X, R):
+    """Step 0.  X [..., d] float32 (bf16 inputs widened exactly), R [d, k] float32.
+    Returns (int8 [..., k], amax float32)."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    R = np.ascontiguousarray(R, dtype=np.float32)
+    d, k = R.shape
+    if X.shape[-1] != d:
+        raise ValueError("X and R do not match")
+    rows = X.size // d
+    out = np.empty(X.shape[:-1] + (k,), dtype=np.int8)
+    amax = np.zeros(1, dtype=np.float32)
+    rc = _load().dsao_project_quantize(_p(X), _p(R), rows, d, k, _p(out), _p(amax))
+    if rc:
+        raise ValueError("dsao_project_quantize: bad arguments")
+    return out, np.float32(amax[0])

@@ -19,6 +19,7 @@ DSA_F32, DSA_BF16 = 0, 1
 EXPORTS = [
     "dsa_keep_from_ratio", "dsa_workspace_bytes", "dsa_predict_mask", "dsa_sddmm", "dsa_sparse_softmax",
     "dsa_spmm", "dsa_masked_attention", "dsa_attention_fwd", "dsa_approx_rowmax", "dsa_mfma_i8_sustained",
+    "dsa_project_quantize", "dsa_project_workspace_bytes",
     "dsa_status_string", "dsa_version",
 ]
 
@@ -67,6 +68,10 @@ def lib():
         L.dsa_attention_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dsa_approx_rowmax.restype = i32
         L.dsa_approx_rowmax.argtypes = [shp, vp, vp, vp, vp]
+        L.dsa_project_workspace_bytes.restype = sz
+        L.dsa_project_workspace_bytes.argtypes = [shp]
+        L.dsa_project_quantize.restype = i32
+        L.dsa_project_quantize.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
         L.dsa_mfma_i8_sustained.restype = i32
         L.dsa_mfma_i8_sustained.argtypes = [i32, i32, vp, vp]
         L.dsa_status_string.restype = ctypes.c_char_p
@@ -222,3 +227,17 @@ def dsa_mfma_i8_sustained(blocks: int, iters: int, sink=None):
     _dev(sink, torch.int32, (blocks * 256,))
     _check(lib().dsa_mfma_i8_sustained(blocks, iters, _ptr(sink), _stream()), "dsa_mfma_i8_sustained")
     return 4 * blocks * 4 * iters * 65536
+
+
+def dsa_project_quantize(shape, X, R, Xt=None, ws=None, want_amax=True):
+    """Returns (Xt int8 [B,H,L,k], amax float tensor of one element or None)."""
+    import torch
+    tq, tk, _, _ = _dims(shape)
+    _dev(X, _qkv_dtype(shape), tq); _dev(R, torch.float32, (shape.d, shape.k))
+    Xt = torch.empty(tk, dtype=torch.int8, device=X.device) if Xt is None else _dev(Xt, torch.int8, tk)
+    need = int(lib().dsa_project_workspace_bytes(ctypes.byref(shape)))
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=X.device) if ws is None else ws
+    amax = torch.empty(1, dtype=torch.float32, device=X.device) if want_amax else None
+    _check(lib().dsa_project_quantize(ctypes.byref(shape), _ptr(X), _ptr(R), _ptr(Xt), _ptr(amax), _ptr(ws),
+                                      ws.numel(), _stream()), "dsa_project_quantize")
+    return Xt, amax

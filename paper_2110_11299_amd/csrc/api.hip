@@ -150,6 +150,25 @@ dsa_status dsa_approx_rowmax(const dsa_shape *sh, const int8_t *Qt, const int8_t
     return from_hip(dsa::launch_rowmax(*sh, Qt, Kt, rowmax, (hipStream_t)stream));
 }
 
+size_t dsa_project_workspace_bytes(const dsa_shape *sh)
+{
+    if (check_predict(sh) != DSA_OK || check_attention(sh) != DSA_OK) return 0;
+    return round_up_256(dsa::project_workspace_bytes(*sh));
+}
+
+dsa_status dsa_project_quantize(const dsa_shape *sh, const void *X, const float *R, int8_t *Xt, float *amax_out,
+                                void *ws, size_t ws_bytes, void *stream)
+{
+    if (!sh || !X || !R || !Xt || !ws) return DSA_ERR_NULL;
+    if (dsa_status s = check_predict(sh)) return s;
+    if (dsa_status s = check_attention(sh)) return s;
+    if (!aligned16(X) || !aligned16(R) || !aligned16(Xt) || !aligned16(ws) ||
+        (reinterpret_cast<uintptr_t>(amax_out) & 3u))
+        return DSA_ERR_ALIGN;
+    if (ws_bytes < round_up_256(dsa::project_workspace_bytes(*sh))) return DSA_ERR_WORKSPACE;
+    return from_hip(dsa::launch_project_quantize(*sh, X, R, Xt, amax_out, ws, (hipStream_t)stream));
+}
+
 dsa_status dsa_mfma_i8_sustained(int32_t blocks, int32_t iters, int32_t *sink, void *stream)
 {
     if (!sink) return DSA_ERR_NULL;

@@ -34,6 +34,10 @@ hipError_t launch_softmax(const dsa_shape &sh, const float *S, float *P, hipStre
 hipError_t launch_rowmax(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *rowmax,
                          hipStream_t st);
 
+hipError_t launch_project_quantize(const dsa_shape &sh, const void *X, const float *R, int8_t *Xt, float *amax_out,
+                                   void *ws, hipStream_t st);
+size_t project_workspace_bytes(const dsa_shape &sh);
+
 hipError_t launch_mfma_i8_stream(int blocks, int iters, int32_t *sink, hipStream_t st);
 
 // Largest `keep` the attention kernels accept (scores of one row are staged in LDS).

@@ -1,0 +1,103 @@
+// The step in front of the prediction path (paper section 3.1, equation 5): reduce a [B,H,L,d]
+// tensor to k dimensions with a projection matrix and quantise to int8.  With no trained
+// predictor weights the projection is one matrix R [d,k]; the quantiser is symmetric per tensor.
+// The arithmetic is fixed so that the int8 codes are reproducible bit for bit:
+//   Y[r,j] = fma(X[r,d-1], R[d-1,j], ... fma(X[r,1], R[1,j], fma(X[r,0], R[0,j], 0)))   in fp32
+//   amax   = max |Y|,   s = 127 / amax  (fp32 division),   code = clip(rint(Y * s), -127, 127)
+// Three launches: clear the maximum, project (Y to scratch, maximum by atomic max on the bit
+// pattern of |Y|, which orders like the value for non-negative floats), quantise.
+#include "dsa_internal.h"
+
+namespace dsa {
+namespace {
+
+constexpr int kProjThreads = 256;
+
+__global__ void clear_word(unsigned *w) { *w = 0u; }
+
+template <typename T> __device__ __forceinline__ float widen(T x);
+template <> __device__ __forceinline__ float widen<float>(float x) { return x; }
+template <> __device__ __forceinline__ float widen<uint16_t>(uint16_t x) { return __uint_as_float((unsigned)x << 16); }
+
+// One thread per (row, four consecutive output columns).
+template <typename T>
+__global__ __launch_bounds__(kProjThreads) void project_rows(const T *__restrict__ X, const float *__restrict__ R,
+                                                             float *__restrict__ Y, unsigned *__restrict__ amax_bits,
+                                                             unsigned rows, int d, int k)
+{
+    extern __shared__ float sR[];                  // [d][k]
+    for (int i = threadIdx.x; i < d * k; i += kProjThreads) sR[i] = R[i];
+    __syncthreads();
+    const int k4 = k / 4;
+    const unsigned item = blockIdx.x * kProjThreads + threadIdx.x;
+    const unsigned r = item / k4;
+    const int j = (item % k4) * 4;
+    float y0 = 0.f, y1 = 0.f, y2 = 0.f, y3 = 0.f;
+    if (r < rows) {
+        const T *x = X + (size_t)r * d;
+        for (int c = 0; c < d; ++c) {
+            const float xc = widen<T>(x[c]);
+            const float4 rc = *reinterpret_cast<const float4 *>(sR + c * k + j);
+            y0 = __fmaf_rn(xc, rc.x, y0);
+            y1 = __fmaf_rn(xc, rc.y, y1);
+            y2 = __fmaf_rn(xc, rc.z, y2);
+            y3 = __fmaf_rn(xc, rc.w, y3);
+        }
+        *reinterpret_cast<float4 *>(Y + (size_t)r * k + j) = make_float4(y0, y1, y2, y3);
+    }
+    float m = fmaxf(fmaxf(fabsf(y0), fabsf(y1)), fmaxf(fabsf(y2), fabsf(y3)));
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
+    if ((threadIdx.x & (kWave - 1)) == 0 && m > 0.f) atomicMax(amax_bits, __float_as_uint(m));
+}
+
+__global__ __launch_bounds__(kProjThreads) void quantize_codes(const float *__restrict__ Y,
+                                                               const unsigned *__restrict__ amax_bits,
+                                                               int8_t *__restrict__ Xt, float *__restrict__ amax_out,
+                                                               size_t n4)
+{
+    const float amax = __uint_as_float(*amax_bits);
+    if (amax_out && blockIdx.x == 0 && threadIdx.x == 0) *amax_out = amax;
+    const float s = amax > 0.f ? __fdiv_rn(127.f, amax) : 0.f;
+    const size_t i = (size_t)blockIdx.x * kProjThreads + threadIdx.x;
+    if (i >= n4) return;
+    const float4 y = reinterpret_cast<const float4 *>(Y)[i];
+    const float q[4] = {y.x, y.y, y.z, y.w};
+    unsigned packed = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float v = fminf(fmaxf(rintf(__fmul_rn(q[e], s)), -127.f), 127.f);
+        packed |= ((unsigned)(int)v & 0xffu) << (8 * e);
+    }
+    reinterpret_cast<unsigned *>(Xt)[i] = packed;
+}
+
+}  // namespace
+
+size_t project_workspace_bytes(const dsa_shape &sh)
+{
+    return (size_t)sh.B * sh.H * sh.L * sh.k * sizeof(float) + 256;
+}
+
+hipError_t launch_project_quantize(const dsa_shape &sh, const void *X, const float *R, int8_t *Xt, float *amax_out,
+                                   void *ws, hipStream_t st)
+{
+    const unsigned rows = (unsigned)sh.B * sh.H * sh.L;
+    const size_t n = (size_t)rows * sh.k;
+    float *Y = static_cast<float *>(ws);
+    unsigned *amax_bits = reinterpret_cast<unsigned *>(static_cast<char *>(ws) + n * sizeof(float));
+    hipLaunchKernelGGL(clear_word, dim3(1), dim3(1), 0, st, amax_bits);
+    const size_t items = n / 4;
+    const dim3 grid((unsigned)((items + kProjThreads - 1) / kProjThreads)), block(kProjThreads);
+    const size_t lds = (size_t)sh.d * sh.k * sizeof(float);
+    if (sh.dtype == DSA_F32)
+        hipLaunchKernelGGL(project_rows<float>, grid, block, lds, st, static_cast<const float *>(X), R, Y, amax_bits,
+                           rows, sh.d, sh.k);
+    else
+        hipLaunchKernelGGL(project_rows<uint16_t>, grid, block, lds, st, static_cast<const uint16_t *>(X), R, Y,
+                           amax_bits, rows, sh.d, sh.k);
+    hipLaunchKernelGGL(quantize_codes, grid, block, 0, st, Y, amax_bits, Xt, amax_out, items);
+    return hipGetLastError();
+}
+
+}  // namespace dsa

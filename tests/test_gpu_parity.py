@@ -223,6 +223,48 @@ def test_rowmax_ragged(dsa, oracle):
         assert np.array_equal(got.cpu().numpy().reshape(-1), want), (L, k)
 
 
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4f", "C5"])
+def test_projection_and_quantiser(dsa, oracle, workload, name):
+    """The step in front of the path: int8 codes bit-exact against the oracle's fp32 recipe,
+    then the whole forward from the GPU-made codes against the oracle run on the oracle-made codes."""
+    import torch
+    x = workload(name)
+    cfg, dev = x.cfg, to_dev(x)
+    sh = shape_of(dsa, cfg)
+    R32 = x.R.astype(np.float32)
+    Rd = torch.from_numpy(R32).cuda()
+    print(f"[project] {name}", flush=True)
+    made = {}
+    for which in ("Q", "K"):
+        codes, amax = dsa.dsa_project_quantize(sh, dev[which], Rd)
+        torch.cuda.synchronize()
+        want, want_amax = oracle.project_quantize(getattr(x, which), R32)
+        assert float(amax.item()) == float(want_amax)
+        assert np.array_equal(codes.cpu().numpy(), want.reshape(codes.shape)), which
+        made[which] = (codes, want)
+    O, idx = dsa.dsa_attention_fwd(sh, dev["Q"], dev["K"], dev["V"], made["Q"][0], made["K"][0])
+    torch.cuda.synchronize()
+    want_O, want_idx = oracle.attention_fwd(x.Q, x.K, x.V, made["Q"][1], made["K"][1], cfg.keep, cfg.scale, cfg.vec)
+    assert np.array_equal(idx.cpu().numpy().reshape(want_idx.shape), want_idx)
+    assert float(np.abs(O.cpu().numpy().reshape(want_O.shape) - want_O).max()) <= TOL[cfg.dtype]
+
+
+def test_projection_ragged_and_zero(dsa, oracle):
+    import torch
+    for (L, d, k, dtype) in [(1, 64, 16, "f32"), (77, 128, 48, "bf16"), (300, 64, 128, "f32")]:
+        cfg = di.custom_config(B=1, H=3, L=L, d=d, dtype=dtype, rank=3, k=k, keep=1, seed=L)
+        x = di.make_inputs(cfg)
+        sh = shape_of(dsa, cfg)
+        R32 = x.R.astype(np.float32)
+        codes, amax = dsa.dsa_project_quantize(sh, to_dev(x)["K"], torch.from_numpy(R32).cuda())
+        want, want_amax = oracle.project_quantize(x.K, R32)
+        assert np.array_equal(codes.cpu().numpy(), want.reshape(codes.shape)) and float(amax.item()) == float(want_amax)
+    sh = dsa.make_shape(1, 1, 32, 64, 16, 1, 1, dsa.DSA_F32, 1.0)
+    codes, amax = dsa.dsa_project_quantize(sh, torch.zeros((1, 1, 32, 64), device="cuda"),
+                                           torch.ones((64, 16), device="cuda"))
+    assert float(amax.item()) == 0.0 and not bool(codes.any())
+
+
 def test_errors_launch_nothing(dsa):
     import torch
     sh = dsa.make_shape(1, 1, 64, 64, 16, 65, 1, dsa.DSA_F32, 0.125)      # keep > L

@@ -30,6 +30,10 @@ MUTANTS = [
      "int64_t n = r / L, i = r % L, g = (i / vec + 1) % G;"),
     ("list not sorted ascending", "qsort(out, (size_t)keep, sizeof(int32_t), by_int32);", ";"),
     ("keep rounds down", "floor(ratio * (double)L + 0.5)", "floor(ratio * (double)L)"),
+    ("codes truncated instead of rounded", "float v = rintf(Y[t] * s);", "float v = truncf(Y[t] * s);"),
+    ("quantiser range 128", "amax > 0.0f ? 127.0f / amax : 0.0f", "amax > 0.0f ? 128.0f / amax : 0.0f"),
+    ("projection matrix transposed", "y = fmaf(X[r * d + c], R[(int64_t)c * k + j], y);",
+     "y = fmaf(X[r * d + c], R[(int64_t)(j % d) * k + (c % k)], y);"),
 ]
 
 PIN_TESTS = [name for name in dir(pins) if name.startswith("test_")]

@@ -311,3 +311,35 @@ def test_bad_arguments_raise(oracle):
         oracle.predict_mask(Qt, Kt, 9)
     with pytest.raises(ValueError):
         oracle.predict_mask(Qt, Kt, 2, vec=3)
+
+
+# ---------------------------------------------------------------- step 0: projection + int8 quantiser
+def test_projection_quantiser_closed_forms(oracle):
+    # amax = 127 makes the scale exactly 1: the codes are the projected values themselves
+    X = np.array([[1.0, 2.0, 0.0], [0.5, 0.0, 0.0], [1.5, 0.0, 0.0], [2.5, 0.0, 0.0], [-2.5, 0.0, 0.0],
+                  [0.0, 0.0, 127.0], [0.0, 0.0, -127.0]], np.float32)
+    R = np.array([[1.0, -1.0], [10.0, 0.25], [1.0, 0.0]], np.float32)
+    codes, amax = oracle.project_quantize(X, R)
+    assert amax == np.float32(127.0)
+    assert codes.tolist() == [[21, 0], [0, 0], [2, -2], [2, -2], [-2, 2], [127, 0], [-127, 0]]   # halves to even
+    z, a0 = oracle.project_quantize(np.zeros((5, 3), np.float32), R)
+    assert a0 == 0 and not z.any()
+    # operand order: X [rows, d] times R [d, k], not its transpose
+    X2 = np.array([[1.0, 0.0], [0.0, 1.0]], np.float32)
+    R2 = np.array([[127.0, 1.0], [2.0, 3.0]], np.float32)
+    assert oracle.project_quantize(X2, R2)[0].tolist() == [[127, 1], [2, 3]]
+
+
+def test_projection_quantiser_against_float64(oracle, workload):
+    # the fp32 recipe may move a code by one step where float64 lands next to a rounding boundary
+    x = workload("C1")
+    for T, want in ((x.Q, x.Qt), (x.K, x.Kt)):
+        codes, amax = oracle.project_quantize(T, x.R.astype(np.float32))
+        y64 = T.astype(np.float64) @ x.R.astype(np.float32).astype(np.float64)
+        assert abs(float(amax) - np.abs(y64).max()) <= 1e-5 * np.abs(y64).max()
+        ref = di.quantize_int8(y64)
+        diff = np.abs(codes.astype(np.int32) - ref.astype(np.int32))
+        assert diff.max() <= 1 and (diff != 0).mean() < 2e-3
+        # and the workload's own codes (float64 R) are the same up to the same kind of step
+        d2 = np.abs(codes.astype(np.int32) - want.astype(np.int32))
+        assert d2.max() <= 1 and (d2 != 0).mean() < 2e-2
