@@ -138,7 +138,7 @@ def main() -> int:
     sh_f = passes[0]["sh"]
     # the step in front of the path (not part of the timed step: Q~, K~ are inputs of the path)
     Rd = torch.from_numpy(x.R.astype(np.float32)).cuda()
-    pws = torch.empty(pkg.binding.lib().dsa_project_workspace_bytes(sh_f), dtype=torch.uint8, device="cuda")
+    pws = torch.empty(pkg.binding.project_workspace_bytes(sh_f), dtype=torch.uint8, device="cuda")
     Qt2, Kt2 = torch.empty_like(Qt), torch.empty_like(Kt)
 
     def project_both():

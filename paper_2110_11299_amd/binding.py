@@ -102,6 +102,10 @@ def workspace_bytes(shape: DsaShape) -> int:
     return int(lib().dsa_workspace_bytes(ctypes.byref(shape)))
 
 
+def project_workspace_bytes(shape: DsaShape) -> int:
+    return int(lib().dsa_project_workspace_bytes(ctypes.byref(shape)))
+
+
 def _check(status: int, where: str):
     if status != DSA_OK:
         raise DsaError(status, where)
@@ -235,7 +239,7 @@ def dsa_project_quantize(shape, X, R, Xt=None, ws=None, want_amax=True):
     tq, tk, _, _ = _dims(shape)
     _dev(X, _qkv_dtype(shape), tq); _dev(R, torch.float32, (shape.d, shape.k))
     Xt = torch.empty(tk, dtype=torch.int8, device=X.device) if Xt is None else _dev(Xt, torch.int8, tk)
-    need = int(lib().dsa_project_workspace_bytes(ctypes.byref(shape)))
+    need = project_workspace_bytes(shape)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=X.device) if ws is None else ws
     amax = torch.empty(1, dtype=torch.float32, device=X.device) if want_amax else None
     _check(lib().dsa_project_quantize(ctypes.byref(shape), _ptr(X), _ptr(R), _ptr(Xt), _ptr(amax), _ptr(ws),

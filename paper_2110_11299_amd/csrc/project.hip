@@ -15,16 +15,38 @@ constexpr int kProjThreads = 256;
 
 __global__ void clear_word(unsigned *w) { *w = 0u; }
 
-template <typename T> __device__ __forceinline__ float widen(T x);
-template <> __device__ __forceinline__ float widen<float>(float x) { return x; }
-template <> __device__ __forceinline__ float widen<uint16_t>(uint16_t x) { return __uint_as_float((unsigned)x << 16); }
+// 16 bytes of a row widened to fp32.
+template <typename T> struct Chunk;
+template <> struct Chunk<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void load(const float *p, float (&v)[4])
+    {
+        const float4 x = *reinterpret_cast<const float4 *>(p);
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+    }
+};
+template <> struct Chunk<uint16_t> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void load(const uint16_t *p, float (&v)[8])
+    {
+        const uint4 x = *reinterpret_cast<const uint4 *>(p);
+        const unsigned w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
 
-// One thread per (row, four consecutive output columns).
+// One thread per (row, four consecutive output columns).  The row is read 16 bytes at a time; the
+// four chains still take their terms in increasing c.
 template <typename T>
 __global__ __launch_bounds__(kProjThreads) void project_rows(const T *__restrict__ X, const float *__restrict__ R,
                                                              float *__restrict__ Y, unsigned *__restrict__ amax_bits,
                                                              unsigned rows, int d, int k)
 {
+    constexpr int E = Chunk<T>::N;
     extern __shared__ float sR[];                  // [d][k]
     for (int i = threadIdx.x; i < d * k; i += kProjThreads) sR[i] = R[i];
     __syncthreads();
@@ -35,20 +57,27 @@ __global__ __launch_bounds__(kProjThreads) void project_rows(const T *__restrict
     float y0 = 0.f, y1 = 0.f, y2 = 0.f, y3 = 0.f;
     if (r < rows) {
         const T *x = X + (size_t)r * d;
-        for (int c = 0; c < d; ++c) {
-            const float xc = widen<T>(x[c]);
-            const float4 rc = *reinterpret_cast<const float4 *>(sR + c * k + j);
-            y0 = __fmaf_rn(xc, rc.x, y0);
-            y1 = __fmaf_rn(xc, rc.y, y1);
-            y2 = __fmaf_rn(xc, rc.z, y2);
-            y3 = __fmaf_rn(xc, rc.w, y3);
+        for (int c0 = 0; c0 < d; c0 += E) {
+            float xv[E];
+            Chunk<T>::load(x + c0, xv);
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const float4 rc = *reinterpret_cast<const float4 *>(sR + (c0 + e) * k + j);
+                y0 = __fmaf_rn(xv[e], rc.x, y0);
+                y1 = __fmaf_rn(xv[e], rc.y, y1);
+                y2 = __fmaf_rn(xv[e], rc.z, y2);
+                y3 = __fmaf_rn(xv[e], rc.w, y3);
+            }
         }
         *reinterpret_cast<float4 *>(Y + (size_t)r * k + j) = make_float4(y0, y1, y2, y3);
     }
     float m = fmaxf(fmaxf(fabsf(y0), fabsf(y1)), fmaxf(fabsf(y2), fabsf(y3)));
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
-    if ((threadIdx.x & (kWave - 1)) == 0 && m > 0.f) atomicMax(amax_bits, __float_as_uint(m));
+    // the atomic only when it can still raise the maximum: after the first few wavefronts almost
+    // none can, and the one hot address stops being a bottleneck
+    if ((threadIdx.x & (kWave - 1)) == 0 && __float_as_uint(m) > __atomic_load_n(amax_bits, __ATOMIC_RELAXED))
+        atomicMax(amax_bits, __float_as_uint(m));
 }
 
 __global__ __launch_bounds__(kProjThreads) void quantize_codes(const float *__restrict__ Y,
