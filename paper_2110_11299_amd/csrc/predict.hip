@@ -270,6 +270,52 @@ __device__ __forceinline__ int unit_key_score(const int *__restrict__ qu, const 
     return s;
 }
 
+// Number of (register, lane) pairs with v >= t for a wavefront-uniform t.  The compares are issued
+// back to back into separate mask registers and counted afterwards: with one shared mask register
+// every compare would wait for the scalar count of the one before it.
+__device__ __forceinline__ int count_ge4(int a, int b, int c, int d, int t)
+{
+    unsigned long long m0, m1, m2, m3;
+    asm("v_cmp_ge_i32_e64 %0, %4, %8\n\tv_cmp_ge_i32_e64 %1, %5, %8\n\t"
+        "v_cmp_ge_i32_e64 %2, %6, %8\n\tv_cmp_ge_i32_e64 %3, %7, %8"
+        : "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3)
+        : "v"(a), "v"(b), "v"(c), "v"(d), "s"(t));
+    return (__popcll(m0) + __popcll(m1)) + (__popcll(m2) + __popcll(m3));
+}
+__device__ __forceinline__ int count_ge8(int a, int b, int c, int d, int e, int f, int g, int h, int t)
+{
+    unsigned long long m0, m1, m2, m3, m4, m5, m6, m7;
+    asm("v_cmp_ge_i32_e64 %0, %8, %16\n\tv_cmp_ge_i32_e64 %1, %9, %16\n\t"
+        "v_cmp_ge_i32_e64 %2, %10, %16\n\tv_cmp_ge_i32_e64 %3, %11, %16\n\t"
+        "v_cmp_ge_i32_e64 %4, %12, %16\n\tv_cmp_ge_i32_e64 %5, %13, %16\n\t"
+        "v_cmp_ge_i32_e64 %6, %14, %16\n\tv_cmp_ge_i32_e64 %7, %15, %16"
+        : "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3), "=&s"(m4), "=&s"(m5), "=&s"(m6), "=&s"(m7)
+        : "v"(a), "v"(b), "v"(c), "v"(d), "v"(e), "v"(f), "v"(g), "v"(h), "s"(t));
+    return ((__popcll(m0) + __popcll(m1)) + (__popcll(m2) + __popcll(m3))) +
+           ((__popcll(m4) + __popcll(m5)) + (__popcll(m6) + __popcll(m7)));
+}
+__device__ __forceinline__ int count_ge2(int a, int b, int t)
+{
+    unsigned long long m0, m1;
+    asm("v_cmp_ge_i32_e64 %0, %2, %4\n\tv_cmp_ge_i32_e64 %1, %3, %4"
+        : "=&s"(m0), "=&s"(m1)
+        : "v"(a), "v"(b), "s"(t));
+    return __popcll(m0) + __popcll(m1);
+}
+template <int NR, int USED>
+__device__ __forceinline__ int count_ge(const int (&v)[NR], int t)
+{
+    int cnt = 0;
+    int i = 0;
+#pragma unroll
+    for (; i + 8 <= USED; i += 8)
+        cnt += count_ge8(v[i], v[i + 1], v[i + 2], v[i + 3], v[i + 4], v[i + 5], v[i + 6], v[i + 7], t);
+    if (USED - i >= 4) { cnt += count_ge4(v[i], v[i + 1], v[i + 2], v[i + 3], t); i += 4; }
+    if (USED - i >= 2) { cnt += count_ge2(v[i], v[i + 1], t); i += 2; }
+    if (USED - i >= 1) cnt += __popcll(__ballot(v[i] >= t));
+    return cnt;
+}
+
 // The keep-th largest of the values a wavefront holds in registers (NR per lane, unused slots
 // INT32_MIN): the largest T with count(v >= T) >= keep, by bisection on the value.  lo and hi are
 // wavefront-uniform; needs count(v >= lo) >= keep and hi >= every value.  Every probe is above
@@ -280,18 +326,18 @@ __device__ __forceinline__ int kth_largest(const int (&v)[NR], int keep, int lo,
 {
     lo = __builtin_amdgcn_readfirstlane(lo);
     hi = __builtin_amdgcn_readfirstlane(hi);
-    while (lo < hi) {
-        const unsigned range = (unsigned)hi - (unsigned)lo;
-        const int mid = lo + (int)((range >> 1) + (range & 1u));
-        int cnt = 0;
-#pragma unroll
-        for (int i = 0; i < USED; ++i) cnt += __popcll(__ballot(v[i] >= mid));
-        if (cnt >= keep) {
-            lo = mid;
-            if (cnt <= keep + slack) break;     // slack > 0: any T with keep <= count(v >= T) <= keep + slack will do
-        } else {
-            hi = mid - 1;
-        }
+    // One exit test per round keeps the loop a handful of scalar instructions around the compares;
+    // the scalar unit is shared by all wavefronts of the compute unit and they all sit in this loop
+    // at the same time.  |values| < 2^30, so lo + hi cannot overflow.
+    bool more = lo < hi;
+    while (more) {
+        const int mid = (lo + hi + 1) >> 1;
+        const int cnt = count_ge<NR, USED>(v, mid);
+        const bool ge = cnt >= keep;
+        lo = ge ? mid : lo;
+        hi = ge ? hi : mid - 1;
+        // slack > 0: any T with keep <= count(v >= T) <= keep + slack will do
+        more = lo < hi && (unsigned)(cnt - keep) > (unsigned)slack;
     }
     return lo;
 }
@@ -323,16 +369,21 @@ __device__ __forceinline__ void score_chunk(v4i (&acc)[TC], int (&bmax)[NB], con
 {
     typedef Mfma<KSTEP> M;
     constexpr int BATCH = 8;
+    // Byte offsets inside the head (L * k <= 4 MB) on top of the wavefront-uniform base pointer: one
+    // 32-bit add per key row instead of a 64-bit multiply.
+    const unsigned off0 = (unsigned)op_lo * (unsigned)k;
+    const unsigned tile_step = 4u * (unsigned)k;
+    const unsigned off_last = (unsigned)(L - 1) * (unsigned)k;
 #pragma unroll
     for (int t0 = 0; t0 < TC; t0 += BATCH) {
         typename M::op_t kop[BATCH];
-        const int8_t *krow[BATCH];
+        unsigned krow[BATCH];
 #pragma unroll
         for (int b = 0; b < BATCH; ++b) {
-            int key = op_lo + 4 * (t0 + b);
-            if (TAIL) key = min(key, L - 1);
-            krow[b] = Kh + (size_t)key * k;
-            kop[b] = M::load(krow[b] + koff[0]);
+            unsigned off = off0 + (unsigned)(t0 + b) * tile_step;
+            if (TAIL) off = min(off, off_last);
+            krow[b] = off;
+            kop[b] = M::load(Kh + (size_t)(off + (unsigned)koff[0]));
         }
 #pragma unroll
         for (int b = 0; b < BATCH; ++b) {
@@ -342,7 +393,7 @@ __device__ __forceinline__ void score_chunk(v4i (&acc)[TC], int (&bmax)[NB], con
 #pragma unroll
             for (int s = 1; s < MAXSTEPS; ++s) {
                 if (s < nsteps) {
-                    if (!same_kop) kop[b] = M::load(krow[b] + koff[s]);
+                    if (!same_kop) kop[b] = M::load(Kh + (size_t)(krow[b] + (unsigned)koff[s]));
                     a = M::run(kop[b], qop[s], a);
                 }
             }
@@ -362,7 +413,8 @@ template <int TC, int NB, int KSTEP, int MAXSTEPS, int MAXW>
 __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__restrict__ Qt,
                                                      const int8_t *__restrict__ Kt,
                                                      int32_t *__restrict__ idx, int L, int k, int keep,
-                                                     int vec, int nchunks, int tiles_per_head, int hc_log2)
+                                                     int vec, int nchunks, int tiles_per_head, int hc_log2,
+                                                     unsigned total_tiles)
 {
     typedef Mfma<KSTEP> M;
     static_assert(TC % 8 == 0 && TC % NB == 0, "tile counts");
@@ -389,7 +441,12 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
     int2 *compact = reinterpret_cast<int2 *>(bm) + w * kCompactCap;             // per wavefront, phase D:
                                                                                 // reuses the bm storage
 
-    const unsigned tile = xcd_contiguous(blockIdx.x, gridDim.x);
+    // A workgroup works through tiles blockIdx.x, blockIdx.x + gridDim.x, ...: with one workgroup
+    // resident per compute unit the stores of one tile then drain while the next tile's keys load.
+    // gridDim.x is a multiple of the XCD count whenever it is smaller than total_tiles, so all tiles
+    // of a workgroup map to the XCD it runs on.
+    for (unsigned vt = blockIdx.x; vt < total_tiles; vt += gridDim.x) {
+    const unsigned tile = xcd_contiguous(vt, total_tiles);
     const unsigned n = tile / (unsigned)tiles_per_head;
     const int u0 = (int)(tile % (unsigned)tiles_per_head) * kTileUnits;
     const int G = L / vec;
@@ -445,22 +502,39 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
         if (DSA_PREDICT_STOP == 1) continue;
         __syncthreads();
         PHASE_MARK(1);
+        // Buckets follow key order inside the chunk, so the ones that hold a real key are the first
+        // `real` of them; the others keep INT32_MIN.
+        const int bucket_keys = 4 * TC / NB;
+        const int real = min(NBT, max(0, (L - chunk_base + bucket_keys - 1) / bucket_keys));
+        constexpr int VB = NB * MAXW / 16;  // NBT <= 4 * MAXW * NB values over 64 lanes
+        const bool dense = real == NBT && NBT == VB * kWave;
         for (int uu = w; uu < kTileUnits; uu += W) {
             const int *v = bm + uu * NBTp;
-            constexpr int VB = NB * MAXW / 16;  // NBT <= 4 * MAXW * NB values over 64 lanes
             int vb[VB];
-#pragma unroll
-            for (int i = 0; i < VB; ++i) vb[i] = v[min(i * kWave + lane, NBT - 1)];
-            int lo = INT32_MAX, hi = INT32_MIN, real = 0;
-#pragma unroll
-            for (int i = 0; i < VB; ++i) {
-                if (i * kWave + lane >= NBT) vb[i] = INT32_MIN;
-                if (vb[i] != INT32_MIN) lo = min(lo, vb[i]);      // buckets of padding keys hold INT32_MIN
-                hi = max(hi, vb[i]);
-                real += __popcll(__ballot(vb[i] != INT32_MIN));
-            }
             int T = INT32_MIN;
-            if (real >= keep) T = kth_largest_of<VB>(vb, (NBT + kWave - 1) / kWave, keep, wave_min(lo), wave_max(hi), keep >> 4);
+            if (dense) {
+#pragma unroll
+                for (int i = 0; i < VB; ++i) vb[i] = v[i * kWave + lane];
+                int lo = vb[0], hi = vb[0];
+#pragma unroll
+                for (int i = 1; i < VB; ++i) {
+                    lo = min(lo, vb[i]);
+                    hi = max(hi, vb[i]);
+                }
+                if (real >= keep) T = kth_largest<VB>(vb, keep, wave_min(lo), wave_max(hi), keep >> 4);
+            } else {
+#pragma unroll
+                for (int i = 0; i < VB; ++i) vb[i] = v[min(i * kWave + lane, NBT - 1)];
+                int lo = INT32_MAX, hi = INT32_MIN;
+#pragma unroll
+                for (int i = 0; i < VB; ++i) {
+                    if (i * kWave + lane >= real) vb[i] = INT32_MIN;
+                    else lo = min(lo, vb[i]);
+                    hi = max(hi, vb[i]);
+                }
+                if (real >= keep)
+                    T = kth_largest_of<VB>(vb, (NBT + kWave - 1) / kWave, keep, wave_min(lo), wave_max(hi), keep >> 4);
+            }
             if (lane == 0) T0s[uu] = max(T0s[uu], T);
         }
         PHASE_MARK(2);
@@ -500,7 +574,7 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
         PHASE_MARK(4);
         // bm / T0s are rewritten only after the next chunk's first barrier
     }
-    if (DSA_PREDICT_STOP >= 1 && DSA_PREDICT_STOP <= 3) return;
+    if (DSA_PREDICT_STOP >= 1 && DSA_PREDICT_STOP <= 3) { __syncthreads(); continue; }
     __syncthreads();
     PHASE_MARK(5);
 
@@ -528,41 +602,72 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
             // candidates in key order as (score, key) pairs; a lane takes two bitmap words per round
             int rank_base = 0;
             for (int w0 = 0; w0 < NW; w0 += 2 * kWave) {
-                const int wi = w0 + 2 * lane;
-                const unsigned m0 = wi < NW ? bw[wi] : 0u;
-                const unsigned m1 = wi + 1 < NW ? bw[wi + 1] : 0u;
-                const int cnt = __popc(m0) + __popc(m1);
+                const int wi = w0 + 2 * lane;           // even; NW is a multiple of 4
+                const bool live = wi < NW;
+                const int wic = min(wi, NW - 2);
+                const unsigned m0 = live ? bw[wic] : 0u;
+                const unsigned m1 = live ? bw[wic + 1] : 0u;
+                const int c0 = __popc(m0), c1 = __popc(m1);
                 int round_total;
-                const int incl = wave_incl_scan(cnt, lane, &round_total);
-                int r = rank_base + incl - cnt;
+                const int incl = wave_incl_scan(c0 + c1, lane, &round_total);
+                const int r = rank_base + incl - (c0 + c1);
                 rank_base += round_total;
+                // holder of each word and the slot of the word's first entry in the holder's segment
+                // (the writer's rotation plus the entries of the holder's earlier words)
+                const int hold0 = wic / WPH;
+                const int hold1 = WPH == 1 ? wic + 1 : hold0;
+                int o0 = uu + 16 * (hold0 & 3) + (hold0 >> 2);
+                if (WPH == 4 && (wic & 2)) o0 += __popc(bw[wic - 1]) + __popc(bw[wic - 2]);
+                const int o1 = WPH == 1 ? uu + 16 * (hold1 & 3) + (hold1 >> 2) : o0 + c0;
+                // HC or more hits in a holder: its segment wrapped and a later non-candidate overwrote
+                // the first entry; such a holder's few scores are recomputed instead
+                const bool wrapped = (c0 && cu[hold0] >= HC) || (c1 && cu[hold1] >= HC);
+                if (__ballot(wrapped) == 0) {
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    const int wj = wi + half;
-                    unsigned m = half ? m1 : m0;
-                    if (m) {
-                        const int hold = wj / WPH;
-                        int o = 0;                       // entries of this holder before word wj
-                        for (int x = hold * WPH; x < wj; ++x) o += __popc(bw[x]);
+                    for (int half = 0; half < 2; ++half) {
+                        unsigned m = half ? m1 : m0;
+                        const int cw = half ? c1 : c0;
+                        const int o = half ? o1 : o0;
+                        const int *src = sg + ((half ? hold1 : hold0) << hc_log2);
+                        int2 *dst = compact + r + (half ? c0 : 0);
+                        const int key0 = (wic + half) * 32;
+                        // the same trip count for every lane, two entries a trip: both segment reads
+                        // are in flight before the first write
+                        for (int t = 0; __ballot(t < cw) != 0; t += 2) {
+                            const int v0 = src[(o + t) & (HC - 1)];
+                            const int v1 = src[(o + t + 1) & (HC - 1)];
+                            const int b0 = __ffs(m) - 1;
+                            m &= m - 1;
+                            const int b1 = __ffs(m) - 1;
+                            m &= m - 1;
+                            if (t < cw) dst[t] = make_int2(v0, key0 + b0);
+                            if (t + 1 < cw) dst[t + 1] = make_int2(v1, key0 + b1);
+                        }
+                    }
+                } else {
+                    int rr = r;
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {
+                        unsigned m = half ? m1 : m0;
+                        const int hold = half ? hold1 : hold0;
+                        int o = half ? o1 : o0;
                         const int *src = sg + (hold << hc_log2);
-                        // HC or more hits: the segment wrapped and a later non-candidate overwrote its
-                        // first entry; such a holder's few scores are recomputed instead
-                        const bool wrapped = cu[hold] >= HC;
-                        o += uu + 16 * (hold & 3) + (hold >> 2);     // the writer's rotation
+                        const bool redo = m && cu[hold] >= HC;
                         while (m) {
                             const int bit = __ffs(m) - 1;
                             m &= m - 1;
-                            const int key = wj * 32 + bit;
-                            const int sc1 = wrapped ? unit_key_score(qu, Kh + (size_t)key * k, vec, k4)
-                                                    : src[o & (HC - 1)];
+                            const int key = (wic + half) * 32 + bit;
+                            const int sc1 = redo ? unit_key_score(qu, Kh + (size_t)key * k, vec, k4)
+                                                 : src[o & (HC - 1)];
                             ++o;
-                            compact[r++] = make_int2(sc1, key);
+                            compact[rr++] = make_int2(sc1, key);
                         }
                     }
                 }
             }
             wave_lds_sync();
             PHASE_MARK(6);
+            if (DSA_PREDICT_STOP == 4) { if (lane == 0) out[0] = compact[nc - 1].x; continue; }
             constexpr int NR = kCompactCap / kWave;
             const int groups = (nc + kWave - 1) / kWave;
             int sc[NR], ck[NR];
@@ -582,6 +687,7 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
             // every candidate reaches T0 and there are at least keep of them
             const int T = kth_largest_of<NR>(sc, groups, keep, T0, wave_max(hi));
             PHASE_MARK(8);
+            if (DSA_PREDICT_STOP == 5) { if (lane == 0) out[0] = T; continue; }
             int gt = 0;
 #pragma unroll
             for (int b = 0; b < NR; ++b)
@@ -637,6 +743,8 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
                 eq_base += __popcll(meq);
             }
         }
+    }
+    __syncthreads();      // the next tile reuses every LDS array
     }
     PHASE_FLUSH();
 }
@@ -698,8 +806,20 @@ hipError_t launch_tiles_t(const TilePlan &p, const dsa_shape &sh, const int8_t *
         if (e != hipSuccess) return e;
     }
     const unsigned tiles = (unsigned)sh.B * sh.H * p.tiles_per_head;
-    hipLaunchKernelGGL(kern, dim3(tiles), dim3(p.W * kWave), p.lds, st, Qt, Kt, idx, sh.L, sh.k, sh.keep,
-                       sh.vec, p.nchunks, p.tiles_per_head, p.hc_log2);
+    // one workgroup per compute unit (a multiple of the XCD count), each looping over tiles
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipError_t e = hipGetDevice(&dev)) return e;
+    if (hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) return e;
+    if (hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kern),
+                                                                    p.W * kWave, p.lds))
+        return e;
+    // Looping pays when a compute unit holds a single workgroup (nothing else hides the start and the
+    // end of a tile); with several resident workgroups the hardware already overlaps them.
+    unsigned resident = per_cu == 1 ? (unsigned)(cus > 0 ? cus : 0) : 0u;
+    resident -= resident % kXcds;
+    const unsigned grid = (resident == 0 || tiles <= resident) ? tiles : resident;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(p.W * kWave), p.lds, st, Qt, Kt, idx, sh.L, sh.k, sh.keep,
+                       sh.vec, p.nchunks, p.tiles_per_head, p.hc_log2, tiles);
     return hipGetLastError();
 }
 
