@@ -27,6 +27,8 @@ if str(ROOT) not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+# plain vector ALU: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz = one 32-bit lane operation each
+ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 
 # HBM traffic of one launch of the dominant kernel (attention_rows at C4f), measured with two
 # rocprofv3 --pmc runs of `bench.py --pmc-mode` (FETCH_SIZE, then WRITE_SIZE), each scaled by what the
@@ -42,6 +44,13 @@ def gather_bytes(cfg) -> int:
     G = cfg.units
     rows = cfg.N * cfg.L
     return 2 * G * cfg.keep * cfg.d * e + rows * cfg.d * e + rows * cfg.d * 4 + G * cfg.keep * 4
+
+
+def compulsory_bytes(cfg) -> int:
+    """Q, K, V and the index lists read once, O written once: what must cross the HBM interface."""
+    e = 4 if cfg.dtype == "f32" else 2
+    rows = cfg.N * cfg.L
+    return 3 * rows * cfg.d * e + rows * cfg.d * 4 + cfg.units * cfg.keep * 4
 
 
 def main() -> int:
@@ -127,14 +136,33 @@ def main() -> int:
         return sum(evs[i].elapsed_time(evs[i + 1]) for i in range(reps)) / reps   # ms
 
     reps = max(args.steps, 5)
+
+    def stage_times(cfg, shc, q, kk, v, qt, kt, o, ix, wsc):
+        """Every kernel of one configuration: the fused path and the staged entry points."""
+        S = torch.empty((cfg.B, cfg.H, cfg.L, cfg.keep), dtype=torch.float32, device="cuda")
+        st = dict(
+            predict_ms=timed(lambda: pkg.dsa_predict_mask(shc, qt, kt, idx=ix, ws=wsc), reps),
+            attention_ms=timed(lambda: pkg.dsa_masked_attention(shc, q, kk, v, ix, O=o), reps),
+            fwd_ms=timed(lambda: pkg.dsa_attention_fwd(shc, q, kk, v, qt, kt, O=o, idx_out=ix, ws=wsc), reps),
+            staged_sddmm_ms=timed(lambda: pkg.dsa_sddmm(shc, q, kk, ix, S=S), reps),
+            staged_softmax_ms=timed(lambda: pkg.dsa_sparse_softmax(shc, S, P=S), reps),
+            staged_spmm_ms=timed(lambda: pkg.dsa_spmm(shc, S, ix, v, O=o), reps))
+        st["heads_seqs_per_s"] = cfg.N / (st["fwd_ms"] * 1e-3)
+        st["attention_gather_GBs"] = gather_bytes(cfg) / (st["attention_ms"] * 1e-3) / 1e9
+        st["attention_frac_hbm"] = st["attention_gather_GBs"] / HBM_PEAK_GBS
+        st["attention_compulsory_GBs"] = compulsory_bytes(cfg) / (st["attention_ms"] * 1e-3) / 1e9
+        ops = 2.0 * cfg.N * cfg.L * cfg.L * cfg.k
+        st["predict_int8_TOPS"] = ops / (st["predict_ms"] * 1e-3) / 1e12
+        st["predict_frac_int8"] = st["predict_int8_TOPS"] / INT8_PEAK_TOPS
+        # the predictor is bound by the selection: one inspection of every (unit, key) score at least
+        scores = float(cfg.N) * (cfg.L // cfg.vec) * cfg.L
+        st["predict_Gscores_per_s"] = scores / (st["predict_ms"] * 1e-3) / 1e9
+        st["predict_frac_alu"] = st["predict_Gscores_per_s"] * 1e9 / ALU_PEAK_LANE_OPS
+        return st
+
     stages = {}
     for p in passes:
-        name = p["cfg"].name
-        stages[name] = dict(
-            predict_ms=timed(lambda: pkg.dsa_predict_mask(p["sh"], Qt, Kt, idx=p["idx"], ws=p["ws"]), reps),
-            attention_ms=timed(lambda: pkg.dsa_masked_attention(p["sh"], Q, K, V, p["idx"], O=p["O"]), reps),
-            fwd_ms=timed(lambda: pkg.dsa_attention_fwd(p["sh"], Q, K, V, Qt, Kt, O=p["O"], idx_out=p["idx"],
-                                                       ws=p["ws"]), reps))
+        stages[p["cfg"].name] = stage_times(p["cfg"], p["sh"], Q, K, V, Qt, Kt, p["O"], p["idx"], p["ws"])
     sh_f = passes[0]["sh"]
     # the step in front of the path (not part of the timed step: Q~, K~ are inputs of the path)
     Rd = torch.from_numpy(x.R.astype(np.float32)).cuda()
@@ -150,14 +178,6 @@ def main() -> int:
     contraction_ms = timed(lambda: pkg.dsa_approx_rowmax(sh_f, Qt, Kt, rowmax=rowmax), reps)
 
     int8_ops = 2.0 * cf.N * cf.L * cf.L * cf.k
-    for name, p in zip(stages, passes):
-        cfg = p["cfg"]
-        st = stages[name]
-        st["heads_seqs_per_s"] = cfg.N / (st["fwd_ms"] * 1e-3)
-        st["attention_gather_GBs"] = gather_bytes(cfg) / (st["attention_ms"] * 1e-3) / 1e9
-        st["attention_frac_hbm"] = st["attention_gather_GBs"] / HBM_PEAK_GBS
-        st["predict_int8_TOPS"] = int8_ops / (st["predict_ms"] * 1e-3) / 1e12
-        st["predict_frac_int8"] = st["predict_int8_TOPS"] / INT8_PEAK_TOPS
     contraction = dict(kernel="dsa_approx_rowmax", workload="C4: N=16 heads*seqs, L=4096, k=32", ms=contraction_ms,
                        int8_TOPS=int8_ops / (contraction_ms * 1e-3) / 1e12)
     contraction["frac_int8"] = contraction["int8_TOPS"] / INT8_PEAK_TOPS
@@ -179,11 +199,21 @@ def main() -> int:
     mfma_ms = timed(lambda: pkg.dsa_mfma_i8_sustained(2048, 2048, sink), 3)
     contraction["mfma_i8_sustained_TOPS"] = mfma_ops / (mfma_ms * 1e-3) / 1e12
 
+    # what a plain device copy reaches on this chip (bytes read + bytes written per second)
+    csrc = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    cdst = torch.empty_like(csrc)
+    cdst.copy_(csrc)
+    copy_ms = timed(lambda: cdst.copy_(csrc), 5)
+    copy_GBs = 2.0 * csrc.numel() / (copy_ms * 1e-3) / 1e9
+    del csrc, cdst
+
     dom = stages["C4f"]
     roofline = dict(kernel="attention_rows (fine-grained SDDMM+softmax+SpMM)", bound="hbm",
                     achieved=dom["attention_gather_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=dom["attention_frac_hbm"], traffic=MEASURED_TRAFFIC_BYTES,
-                    algorithmic_bytes=gather_bytes(cf), avg_launch_ms=dom["attention_ms"])
+                    algorithmic_bytes=gather_bytes(cf), avg_launch_ms=dom["attention_ms"],
+                    compulsory_bytes=compulsory_bytes(cf), compulsory_GBs=dom["attention_compulsory_GBs"],
+                    device_copy_GBs=copy_GBs)
 
     all_configs = None
     if args.all_configs:
@@ -202,12 +232,7 @@ def main() -> int:
             ix = torch.empty((cfg.B, cfg.H, cfg.L // cfg.vec, cfg.keep), dtype=torch.int32, device="cuda")
             wsc = pkg.binding.alloc_workspace(shc)
             pkg.dsa_attention_fwd(shc, q, kk, v, qt, kt, O=o, idx_out=ix, ws=wsc)
-            st = dict(predict_ms=timed(lambda: pkg.dsa_predict_mask(shc, qt, kt, idx=ix, ws=wsc), reps),
-                      attention_ms=timed(lambda: pkg.dsa_masked_attention(shc, q, kk, v, ix, O=o), reps),
-                      fwd_ms=timed(lambda: pkg.dsa_attention_fwd(shc, q, kk, v, qt, kt, O=o, idx_out=ix, ws=wsc), reps))
-            st["heads_seqs_per_s"] = cfg.N / (st["fwd_ms"] * 1e-3)
-            st["attention_gather_GBs"] = gather_bytes(cfg) / (st["attention_ms"] * 1e-3) / 1e9
-            st["predict_int8_TOPS"] = 2.0 * cfg.N * cfg.L * cfg.L * cfg.k / (st["predict_ms"] * 1e-3) / 1e12
+            st = stage_times(cfg, shc, q, kk, v, qt, kt, o, ix, wsc)
             all_configs[name] = st
             del q, kk, v, qt, kt, o, ix, wsc
 

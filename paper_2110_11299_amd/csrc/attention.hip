@@ -172,6 +172,10 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
         if (MODE == kSddmm) return;
         m = groups_max<LPR>(m);
         __syncthreads();
+        // unnormalised weights, computed once per kept key (the lanes that share a value row would
+        // otherwise each repeat the exponential)
+        for (int t = lane; t < keep; t += kWave) sc[t] = __expf(sc[t] - m);
+        __syncthreads();
     }
 
     float o[E], z = 0.f;
@@ -187,7 +191,7 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
             const int tt = min(t, keep - 1);
             vv[u] = P::load(Vh + (unsigned)(sl[tt] * D + sub * E));
             if (MODE == kSpmm) p[u] = Pin[(size_t)r * keep + tt];
-            else p[u] = __expf(sc[tt] - m);
+            else p[u] = sc[tt];
             p[u] = t < keep ? p[u] : 0.f;
         }
 #pragma unroll
