@@ -174,6 +174,16 @@ def main() -> int:
         pkg.dsa_project_quantize(sh_f, K, Rd, Xt=Kt2, ws=pws, want_amax=False)
 
     project_ms = timed(project_both, reps)
+    # the predictor at the paper's lower precisions (packed INT4 / INT2 codes made on the GPU)
+    low_precision = {}
+    for bits in (4, 2):
+        q_lp, _ = pkg.dsa_project_quantize_bits(sh_f, bits, Q, Rd, ws=pws, want_amax=False)
+        k_lp, _ = pkg.dsa_project_quantize_bits(sh_f, bits, K, Rd, ws=pws, want_amax=False)
+        ws_lp = torch.empty(pkg.binding.predict_workspace_bytes_bits(sh_f, bits), dtype=torch.uint8, device="cuda")
+        idx_lp = torch.empty_like(passes[0]["idx"])
+        low_precision[f"int{bits}"] = dict(
+            predict_ms=timed(lambda: pkg.dsa_predict_mask_bits(sh_f, bits, q_lp, k_lp, idx=idx_lp, ws=ws_lp), reps))
+        del q_lp, k_lp, ws_lp, idx_lp
     rowmax = torch.empty((cf.B, cf.H, cf.L), dtype=torch.int32, device="cuda")
     contraction_ms = timed(lambda: pkg.dsa_approx_rowmax(sh_f, Qt, Kt, rowmax=rowmax), reps)
 
@@ -264,6 +274,8 @@ def main() -> int:
                            heads_seqs_per_step=heads_seqs, seed=cf.seed),
                roofline=roofline, cpu_baseline=cpu_baseline, stages=stages, contraction=contraction,
                all_configs=all_configs,
+               low_precision_predict=dict(what="dsa_predict_mask_bits at C4 fine-grained (unpack to int8 + int8 path)",
+                                          **low_precision),
                project_quantize=dict(what="Q~ and K~ from Q, K and R on the GPU (dsa_project_quantize twice), C4",
                                      ms=project_ms),
                host_cores=len(os.sched_getaffinity(0)), device=torch.cuda.get_device_name(0))

@@ -128,6 +128,24 @@ size_t dsa_project_workspace_bytes(const dsa_shape *shape);
 dsa_status dsa_project_quantize(const dsa_shape *shape, const void *X, const float *R, int8_t *Xt,
                                 float *amax_out, void *ws, size_t ws_bytes, void *stream);
 
+/* Lower prediction precision (section 3.3 sets the prediction precision to INT4; table 2 sweeps
+ * INT2 to INT16 and FP32).  `bits` is 8, 4 or 2.  The codes are the integers of magnitude up to
+ * qmax = 2^(bits-1) - 1 (127, 7, 1), produced as in dsa_project_quantize with s = qmax / amax, and
+ * stored two's complement with 8/bits codes per byte: code j of a row occupies bits
+ * [bits * (j mod 8/bits), + bits) of byte j / (8/bits) of that row, rows contiguous
+ * ([B,H,L,k*bits/8] bytes).  bits = 8 is dsa_project_quantize / dsa_predict_mask.
+ *   dsa_project_quantize_bits: X, R, amax_out, ws as in dsa_project_quantize; Xt receives the
+ *     packed codes.
+ *   dsa_predict_mask_bits: steps (a)+(b) from packed codes.  gfx950 has no 4-bit or 2-bit integer
+ *     matrix instruction, so the codes are widened to int8 in `ws` and the int8 path runs; the
+ *     scores, and therefore the mask, are those of the integer codes exactly.  `ws` holds at least
+ *     dsa_predict_workspace_bytes_bits(). */
+dsa_status dsa_project_quantize_bits(const dsa_shape *shape, int32_t bits, const void *X, const float *R,
+                                     void *Xt, float *amax_out, void *ws, size_t ws_bytes, void *stream);
+size_t dsa_predict_workspace_bytes_bits(const dsa_shape *shape, int32_t bits);
+dsa_status dsa_predict_mask_bits(const dsa_shape *shape, int32_t bits, const void *Qt, const void *Kt,
+                                 int32_t *idx, void *ws, size_t ws_bytes, void *stream);
+
 /* Measurement aid for step (a): runs `blocks` workgroups of 4 wavefronts, each issuing 4*iters
  * independent int8 MFMAs (32x32x32) with no memory traffic, i.e. 4*blocks*4*iters*65536 int8
  * operations in all.  Timing it gives the matrix-core rate the chip sustains at its own clocks,

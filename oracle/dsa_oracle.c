@@ -242,11 +242,14 @@ int32_t dsao_masked_attention(const float *Q, const float *K, const float *V, co
 }
 
 /* Step 0: Xt [rows, k] = quantise(X [rows, d] . R [d, k]); *amax = max |Y|.  fp32 by design (see
- * the header comment): y is built by fmaf in increasing c, exactly one rounding per term. */
-int32_t dsao_project_quantize(const float *X, const float *R, int64_t rows, int32_t d, int32_t k,
-                              int8_t *Xt, float *amax_out)
+ * the header comment): y is built by fmaf in increasing c, exactly one rounding per term.
+ * `bits` is the prediction precision (section 3.3 takes INT4, table 2 sweeps INT2 to INT16): the
+ * codes are the integers of magnitude up to qmax = 2^(bits-1) - 1, one per int8 here. */
+int32_t dsao_project_quantize_bits(const float *X, const float *R, int64_t rows, int32_t d, int32_t k,
+                                   int32_t bits, int8_t *Xt, float *amax_out)
 {
-    if (!X || !R || !Xt || rows < 0 || d < 1 || k < 1) return 1;
+    if (!X || !R || !Xt || rows < 0 || d < 1 || k < 1 || bits < 2 || bits > 8) return 1;
+    const float qmax = (float)((1 << (bits - 1)) - 1);
     float *Y = (float *)malloc(sizeof(float) * (size_t)rows * (size_t)k + 4);
     if (!Y) return 1;
     float amax = 0.0f;
@@ -259,15 +262,55 @@ int32_t dsao_project_quantize(const float *X, const float *R, int64_t rows, int3
             if (fabsf(y) > amax) amax = fabsf(y);
         }
     }
-    const float s = amax > 0.0f ? 127.0f / amax : 0.0f;
+    const float s = amax > 0.0f ? qmax / amax : 0.0f;
 #pragma omp parallel for schedule(static)
     for (int64_t t = 0; t < rows * (int64_t)k; ++t) {
         float v = rintf(Y[t] * s);            /* default rounding mode: halves to even */
-        if (v > 127.0f) v = 127.0f;
-        if (v < -127.0f) v = -127.0f;
+        if (v > qmax) v = qmax;
+        if (v < -qmax) v = -qmax;
         Xt[t] = (int8_t)v;
     }
     if (amax_out) *amax_out = amax;
     free(Y);
+    return 0;
+}
+
+int32_t dsao_project_quantize(const float *X, const float *R, int64_t rows, int32_t d, int32_t k,
+                              int8_t *Xt, float *amax_out)
+{
+    return dsao_project_quantize_bits(X, R, rows, d, k, 8, Xt, amax_out);
+}
+
+/* Storage of low-precision codes: 8/bits codes per byte, two's complement fields, code j of a row
+ * in bits [bits * (j mod 8/bits), + bits) of byte j / (8/bits).  n = number of codes, a multiple of
+ * 8/bits.  bits = 8 copies. */
+int32_t dsao_pack_codes(const int8_t *codes, int64_t n, int32_t bits, uint8_t *packed)
+{
+    if (!codes || !packed || n < 0 || (bits != 2 && bits != 4 && bits != 8)) return 1;
+    const int32_t per = 8 / bits;
+    if (n % per) return 1;
+    const int32_t lim = (1 << (bits - 1)) - 1;
+    for (int64_t b = 0; b < n / per; ++b) {
+        uint32_t byte = 0;
+        for (int32_t f = 0; f < per; ++f) {
+            const int32_t c = codes[b * per + f];
+            if (bits < 8 && (c > lim || c < -lim)) return 2;      /* not representable */
+            byte |= ((uint32_t)c & ((1u << bits) - 1u)) << (bits * f);
+        }
+        packed[b] = (uint8_t)byte;
+    }
+    return 0;
+}
+
+int32_t dsao_unpack_codes(const uint8_t *packed, int64_t n, int32_t bits, int8_t *codes)
+{
+    if (!codes || !packed || n < 0 || (bits != 2 && bits != 4 && bits != 8)) return 1;
+    const int32_t per = 8 / bits;
+    if (n % per) return 1;
+    for (int64_t j = 0; j < n; ++j) {
+        const uint32_t field = ((uint32_t)packed[j / per] >> (bits * (int32_t)(j % per))) & ((1u << bits) - 1u);
+        const int32_t sign = 1 << (bits - 1);
+        codes[j] = (int8_t)(((int32_t)field ^ sign) - sign);      /* sign extension of the field */
+    }
     return 0;
 }

@@ -55,6 +55,12 @@ def _load():
                                               vp, i64, vp, vp, vp]
         lib.dsao_project_quantize.restype = i32
         lib.dsao_project_quantize.argtypes = [vp, vp, i64, i32, i32, vp, vp]
+        lib.dsao_project_quantize_bits.restype = i32
+        lib.dsao_project_quantize_bits.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
+        lib.dsao_pack_codes.restype = i32
+        lib.dsao_pack_codes.argtypes = [vp, i64, i32, vp]
+        lib.dsao_unpack_codes.restype = i32
+        lib.dsao_unpack_codes.argtypes = [vp, i64, i32, vp]
         _lib = lib
     return _lib
 
@@ -202,9 +208,9 @@ def attention_fwd(Q, K, V, Qt, Kt, keep, scale, vec=1):
     return masked_attention(Q, K, V, idx, scale, vec), idx
 
 
-def project_quantize(X, R):
+def project_quantize(X, R, bits=8):
     """Step 0.  X [..., d] float32 (bf16 inputs widened exactly), R [d, k] float32.
-    Returns (int8 [..., k], amax float32)."""
+    Returns (int8 [..., k] with |code| <= 2^(bits-1) - 1, amax float32)."""
     X = np.ascontiguousarray(X, dtype=np.float32)
     R = np.ascontiguousarray(R, dtype=np.float32)
     d, k = R.shape
@@ -213,7 +219,29 @@ def project_quantize(X, R):
     rows = X.size // d
     out = np.empty(X.shape[:-1] + (k,), dtype=np.int8)
     amax = np.zeros(1, dtype=np.float32)
-    rc = _load().dsao_project_quantize(_p(X), _p(R), rows, d, k, _p(out), _p(amax))
+    rc = _load().dsao_project_quantize_bits(_p(X), _p(R), rows, d, k, int(bits), _p(out), _p(amax))
     if rc:
-        raise ValueError("dsao_project_quantize: bad arguments")
+        raise ValueError("dsao_project_quantize_bits: bad arguments")
     return out, np.float32(amax[0])
+
+
+def pack_codes(codes, bits):
+    """int8 codes [..., k] -> uint8 [..., k*bits/8] (8/bits codes per byte, low field first)."""
+    codes = np.ascontiguousarray(codes, dtype=np.int8)
+    per = 8 // bits
+    out = np.empty(codes.shape[:-1] + (codes.shape[-1] // per,), dtype=np.uint8)
+    rc = _load().dsao_pack_codes(_p(codes), codes.size, int(bits), _p(out))
+    if rc:
+        raise ValueError("dsao_pack_codes: bad arguments" if rc == 1 else "dsao_pack_codes: code out of range")
+    return out
+
+
+def unpack_codes(packed, bits):
+    """Inverse of pack_codes."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    per = 8 // bits
+    out = np.empty(packed.shape[:-1] + (packed.shape[-1] * per,), dtype=np.int8)
+    rc = _load().dsao_unpack_codes(_p(packed), out.size, int(bits), _p(out))
+    if rc:
+        raise ValueError("dsao_unpack_codes: bad arguments")
+    return out

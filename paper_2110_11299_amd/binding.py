@@ -20,6 +20,7 @@ EXPORTS = [
     "dsa_keep_from_ratio", "dsa_workspace_bytes", "dsa_predict_mask", "dsa_sddmm", "dsa_sparse_softmax",
     "dsa_spmm", "dsa_masked_attention", "dsa_attention_fwd", "dsa_approx_rowmax", "dsa_mfma_i8_sustained",
     "dsa_project_quantize", "dsa_project_workspace_bytes",
+    "dsa_project_quantize_bits", "dsa_predict_workspace_bytes_bits", "dsa_predict_mask_bits",
     "dsa_status_string", "dsa_version",
 ]
 
@@ -72,6 +73,12 @@ def lib():
         L.dsa_project_workspace_bytes.argtypes = [shp]
         L.dsa_project_quantize.restype = i32
         L.dsa_project_quantize.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
+        L.dsa_project_quantize_bits.restype = i32
+        L.dsa_project_quantize_bits.argtypes = [shp, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.dsa_predict_workspace_bytes_bits.restype = sz
+        L.dsa_predict_workspace_bytes_bits.argtypes = [shp, i32]
+        L.dsa_predict_mask_bits.restype = i32
+        L.dsa_predict_mask_bits.argtypes = [shp, i32, vp, vp, vp, vp, sz, vp]
         L.dsa_mfma_i8_sustained.restype = i32
         L.dsa_mfma_i8_sustained.argtypes = [i32, i32, vp, vp]
         L.dsa_status_string.restype = ctypes.c_char_p
@@ -104,6 +111,10 @@ def workspace_bytes(shape: DsaShape) -> int:
 
 def project_workspace_bytes(shape: DsaShape) -> int:
     return int(lib().dsa_project_workspace_bytes(ctypes.byref(shape)))
+
+
+def predict_workspace_bytes_bits(shape: DsaShape, bits: int) -> int:
+    return int(lib().dsa_predict_workspace_bytes_bits(ctypes.byref(shape), bits))
 
 
 def _check(status: int, where: str):
@@ -245,3 +256,36 @@ def dsa_project_quantize(shape, X, R, Xt=None, ws=None, want_amax=True):
     _check(lib().dsa_project_quantize(ctypes.byref(shape), _ptr(X), _ptr(R), _ptr(Xt), _ptr(amax), _ptr(ws),
                                       ws.numel(), _stream()), "dsa_project_quantize")
     return Xt, amax
+
+
+def _packed_dims(shape: DsaShape, bits: int):
+    return (shape.B, shape.H, shape.L, shape.k * bits // 8)
+
+
+def dsa_project_quantize_bits(shape, bits, X, R, Xt=None, ws=None, want_amax=True):
+    """Returns (packed codes uint8 [B,H,L,k*bits/8], amax float tensor of one element or None)."""
+    import torch
+    tq, _, _, _ = _dims(shape)
+    tp = _packed_dims(shape, bits)
+    _dev(X, _qkv_dtype(shape), tq); _dev(R, torch.float32, (shape.d, shape.k))
+    Xt = torch.empty(tp, dtype=torch.uint8, device=X.device) if Xt is None else _dev(Xt, torch.uint8, tp)
+    need = project_workspace_bytes(shape)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=X.device) if ws is None else ws
+    amax = torch.empty(1, dtype=torch.float32, device=X.device) if want_amax else None
+    _check(lib().dsa_project_quantize_bits(ctypes.byref(shape), bits, _ptr(X), _ptr(R), _ptr(Xt), _ptr(amax),
+                                           _ptr(ws), ws.numel(), _stream()), "dsa_project_quantize_bits")
+    return Xt, amax
+
+
+def dsa_predict_mask_bits(shape, bits, Qt, Kt, idx=None, ws=None):
+    """Mask from packed low-precision codes (uint8 [B,H,L,k*bits/8])."""
+    import torch
+    _, _, ti, _ = _dims(shape)
+    tp = _packed_dims(shape, bits)
+    _dev(Qt, torch.uint8, tp); _dev(Kt, torch.uint8, tp)
+    idx = torch.empty(ti, dtype=torch.int32, device=Qt.device) if idx is None else _dev(idx, torch.int32, ti)
+    if ws is None:
+        ws = torch.empty(max(predict_workspace_bytes_bits(shape, bits), 16), dtype=torch.uint8, device=Qt.device)
+    _check(lib().dsa_predict_mask_bits(ctypes.byref(shape), bits, _ptr(Qt), _ptr(Kt), _ptr(idx), _ptr(ws),
+                                       ws.numel(), _stream()), "dsa_predict_mask_bits")
+    return idx

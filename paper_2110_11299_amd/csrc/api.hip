@@ -156,17 +156,53 @@ size_t dsa_project_workspace_bytes(const dsa_shape *sh)
     return round_up_256(dsa::project_workspace_bytes(*sh));
 }
 
-dsa_status dsa_project_quantize(const dsa_shape *sh, const void *X, const float *R, int8_t *Xt, float *amax_out,
-                                void *ws, size_t ws_bytes, void *stream)
+dsa_status dsa_project_quantize_bits(const dsa_shape *sh, int32_t bits, const void *X, const float *R, void *Xt,
+                                     float *amax_out, void *ws, size_t ws_bytes, void *stream)
 {
     if (!sh || !X || !R || !Xt || !ws) return DSA_ERR_NULL;
+    if (bits != 8 && bits != 4 && bits != 2) return DSA_ERR_UNSUPPORTED;
     if (dsa_status s = check_predict(sh)) return s;
     if (dsa_status s = check_attention(sh)) return s;
     if (!aligned16(X) || !aligned16(R) || !aligned16(Xt) || !aligned16(ws) ||
         (reinterpret_cast<uintptr_t>(amax_out) & 3u))
         return DSA_ERR_ALIGN;
     if (ws_bytes < round_up_256(dsa::project_workspace_bytes(*sh))) return DSA_ERR_WORKSPACE;
-    return from_hip(dsa::launch_project_quantize(*sh, X, R, Xt, amax_out, ws, (hipStream_t)stream));
+    return from_hip(dsa::launch_project_quantize(*sh, bits, X, R, Xt, amax_out, ws, (hipStream_t)stream));
+}
+
+dsa_status dsa_project_quantize(const dsa_shape *sh, const void *X, const float *R, int8_t *Xt, float *amax_out,
+                                void *ws, size_t ws_bytes, void *stream)
+{
+    return dsa_project_quantize_bits(sh, 8, X, R, Xt, amax_out, ws, ws_bytes, stream);
+}
+
+size_t dsa_predict_workspace_bytes_bits(const dsa_shape *sh, int32_t bits)
+{
+    if (check_predict(sh) != DSA_OK || (bits != 8 && bits != 4 && bits != 2)) return 0;
+    const size_t codes = bits == 8 ? 0 : round_up_256((size_t)sh->B * sh->H * sh->L * sh->k);
+    return 2 * codes + round_up_256(dsa::predict_workspace_bytes(*sh));
+}
+
+dsa_status dsa_predict_mask_bits(const dsa_shape *sh, int32_t bits, const void *Qt, const void *Kt, int32_t *idx,
+                                 void *ws, size_t ws_bytes, void *stream)
+{
+    if (!sh || !Qt || !Kt || !idx) return DSA_ERR_NULL;
+    if (bits != 8 && bits != 4 && bits != 2) return DSA_ERR_UNSUPPORTED;
+    if (bits == 8)
+        return dsa_predict_mask(sh, static_cast<const int8_t *>(Qt), static_cast<const int8_t *>(Kt), idx, ws, ws_bytes,
+                                stream);
+    if (dsa_status s = check_predict(sh)) return s;
+    if (!aligned16(Qt) || !aligned16(Kt) || !aligned16(idx) || !aligned16(ws)) return DSA_ERR_ALIGN;
+    const size_t need = dsa_predict_workspace_bytes_bits(sh, bits);
+    if (!ws || ws_bytes < need) return DSA_ERR_WORKSPACE;
+    const size_t n_codes = (size_t)sh->B * sh->H * sh->L * sh->k;
+    const size_t codes = round_up_256(n_codes);
+    int8_t *q8 = static_cast<int8_t *>(ws), *k8 = q8 + codes;
+    void *pws = k8 + codes;
+    hipStream_t st = (hipStream_t)stream;
+    if (hipError_t e = dsa::launch_unpack_codes(bits, Qt, q8, n_codes, st)) return from_hip(e);
+    if (hipError_t e = dsa::launch_unpack_codes(bits, Kt, k8, n_codes, st)) return from_hip(e);
+    return from_hip(dsa::launch_predict(*sh, q8, k8, idx, pws, st));
 }
 
 dsa_status dsa_mfma_i8_sustained(int32_t blocks, int32_t iters, int32_t *sink, void *stream)

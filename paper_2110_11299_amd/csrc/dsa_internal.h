@@ -34,8 +34,9 @@ hipError_t launch_softmax(const dsa_shape &sh, const float *S, float *P, hipStre
 hipError_t launch_rowmax(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *rowmax,
                          hipStream_t st);
 
-hipError_t launch_project_quantize(const dsa_shape &sh, const void *X, const float *R, int8_t *Xt, float *amax_out,
-                                   void *ws, hipStream_t st);
+hipError_t launch_project_quantize(const dsa_shape &sh, int bits, const void *X, const float *R, void *Xt,
+                                   float *amax_out, void *ws, hipStream_t st);
+hipError_t launch_unpack_codes(int bits, const void *packed, int8_t *codes, size_t n_codes, hipStream_t st);
 size_t project_workspace_bytes(const dsa_shape &sh);
 
 hipError_t launch_mfma_i8_stream(int blocks, int iters, int32_t *sink, hipStream_t st);

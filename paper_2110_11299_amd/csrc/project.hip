@@ -3,7 +3,8 @@
 // predictor weights the projection is one matrix R [d,k]; the quantiser is symmetric per tensor.
 // The arithmetic is fixed so that the int8 codes are reproducible bit for bit:
 //   Y[r,j] = fma(X[r,d-1], R[d-1,j], ... fma(X[r,1], R[1,j], fma(X[r,0], R[0,j], 0)))   in fp32
-//   amax   = max |Y|,   s = 127 / amax  (fp32 division),   code = clip(rint(Y * s), -127, 127)
+//   amax   = max |Y|,   s = qmax / amax  (fp32 division),   code = clip(rint(Y * s), -qmax, qmax)
+// with qmax = 127 (int8), 7 (INT4, the paper's default prediction precision, section 3.3) or 1 (INT2).
 // Three launches: clear the maximum, project (Y to scratch, maximum by atomic max on the bit
 // pattern of |Y|, which orders like the value for non-negative floats), quantise.
 #include "dsa_internal.h"
@@ -80,14 +81,18 @@ __global__ __launch_bounds__(kProjThreads) void project_rows(const T *__restrict
         atomicMax(amax_bits, __float_as_uint(m));
 }
 
+// Four codes per thread, BITS wide each, stored two's complement with 8/BITS codes per byte (code j
+// of a row in bits [BITS * (j mod 8/BITS), + BITS) of byte j / (8/BITS)): 4, 2 or 1 byte per thread.
+template <int BITS>
 __global__ __launch_bounds__(kProjThreads) void quantize_codes(const float *__restrict__ Y,
                                                                const unsigned *__restrict__ amax_bits,
-                                                               int8_t *__restrict__ Xt, float *__restrict__ amax_out,
+                                                               uint8_t *__restrict__ Xt, float *__restrict__ amax_out,
                                                                size_t n4)
 {
+    constexpr float kQmax = (float)((1 << (BITS - 1)) - 1);
     const float amax = __uint_as_float(*amax_bits);
     if (amax_out && blockIdx.x == 0 && threadIdx.x == 0) *amax_out = amax;
-    const float s = amax > 0.f ? __fdiv_rn(127.f, amax) : 0.f;
+    const float s = amax > 0.f ? __fdiv_rn(kQmax, amax) : 0.f;
     const size_t i = (size_t)blockIdx.x * kProjThreads + threadIdx.x;
     if (i >= n4) return;
     const float4 y = reinterpret_cast<const float4 *>(Y)[i];
@@ -95,10 +100,39 @@ __global__ __launch_bounds__(kProjThreads) void quantize_codes(const float *__re
     unsigned packed = 0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        const float v = fminf(fmaxf(rintf(__fmul_rn(q[e], s)), -127.f), 127.f);
-        packed |= ((unsigned)(int)v & 0xffu) << (8 * e);
+        const float v = fminf(fmaxf(rintf(__fmul_rn(q[e], s)), -kQmax), kQmax);
+        packed |= ((unsigned)(int)v & ((1u << BITS) - 1u)) << (BITS * e);
     }
-    reinterpret_cast<unsigned *>(Xt)[i] = packed;
+    if (BITS == 8) reinterpret_cast<unsigned *>(Xt)[i] = packed;
+    else if (BITS == 4) reinterpret_cast<uint16_t *>(Xt)[i] = (uint16_t)packed;
+    else Xt[i] = (uint8_t)packed;
+}
+
+// Packed codes back to one int8 per code: a thread expands 4 packed bytes.
+template <int BITS>
+__global__ __launch_bounds__(kProjThreads) void unpack_codes(const unsigned *__restrict__ packed,
+                                                             int8_t *__restrict__ codes, size_t words)
+{
+    constexpr int PER = 32 / BITS;                  // codes in one 32-bit word
+    const size_t i = (size_t)blockIdx.x * kProjThreads + threadIdx.x;
+    if (i >= words) return;
+    const unsigned w = packed[i];
+    unsigned out[PER / 4];
+#pragma unroll
+    for (int o = 0; o < PER / 4; ++o) {
+        unsigned v = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int f = 4 * o + e;
+            // field f to the top of the word, then an arithmetic shift back: sign extension
+            const int c = (int)(w << (32 - BITS * (f + 1))) >> (32 - BITS);
+            v |= ((unsigned)c & 0xffu) << (8 * e);
+        }
+        out[o] = v;
+    }
+    unsigned *dst = reinterpret_cast<unsigned *>(codes) + i * (PER / 4);
+#pragma unroll
+    for (int o = 0; o < PER / 4; ++o) dst[o] = out[o];
 }
 
 }  // namespace
@@ -108,8 +142,8 @@ size_t project_workspace_bytes(const dsa_shape &sh)
     return (size_t)sh.B * sh.H * sh.L * sh.k * sizeof(float) + 256;
 }
 
-hipError_t launch_project_quantize(const dsa_shape &sh, const void *X, const float *R, int8_t *Xt, float *amax_out,
-                                   void *ws, hipStream_t st)
+hipError_t launch_project_quantize(const dsa_shape &sh, int bits, const void *X, const float *R, void *Xt,
+                                   float *amax_out, void *ws, hipStream_t st)
 {
     const unsigned rows = (unsigned)sh.B * sh.H * sh.L;
     const size_t n = (size_t)rows * sh.k;
@@ -125,7 +159,20 @@ hipError_t launch_project_quantize(const dsa_shape &sh, const void *X, const flo
     else
         hipLaunchKernelGGL(project_rows<uint16_t>, grid, block, lds, st, static_cast<const uint16_t *>(X), R, Y,
                            amax_bits, rows, sh.d, sh.k);
-    hipLaunchKernelGGL(quantize_codes, grid, block, 0, st, Y, amax_bits, Xt, amax_out, items);
+    uint8_t *out = static_cast<uint8_t *>(Xt);
+    if (bits == 8) hipLaunchKernelGGL(quantize_codes<8>, grid, block, 0, st, Y, amax_bits, out, amax_out, items);
+    else if (bits == 4) hipLaunchKernelGGL(quantize_codes<4>, grid, block, 0, st, Y, amax_bits, out, amax_out, items);
+    else hipLaunchKernelGGL(quantize_codes<2>, grid, block, 0, st, Y, amax_bits, out, amax_out, items);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack_codes(int bits, const void *packed, int8_t *codes, size_t n_codes, hipStream_t st)
+{
+    const size_t words = n_codes * bits / 32;      // n_codes is a multiple of 16
+    const dim3 grid((unsigned)((words + kProjThreads - 1) / kProjThreads)), block(kProjThreads);
+    const unsigned *src = static_cast<const unsigned *>(packed);
+    if (bits == 4) hipLaunchKernelGGL(unpack_codes<4>, grid, block, 0, st, src, codes, words);
+    else hipLaunchKernelGGL(unpack_codes<2>, grid, block, 0, st, src, codes, words);
     return hipGetLastError();
 }
 

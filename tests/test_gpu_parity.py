@@ -265,6 +265,53 @@ def test_projection_ragged_and_zero(dsa, oracle):
     assert float(amax.item()) == 0.0 and not bool(codes.any())
 
 
+@pytest.mark.parametrize("bits", [4, 2])
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4f", "C5"])
+def test_low_precision_prediction(dsa, oracle, workload, name, bits):
+    """Prediction at INT4 / INT2: packed codes made on the GPU are the oracle's codes in the oracle's
+    packing bit for bit, and the mask found from them is the oracle's mask of those integer codes
+    (few levels: ties at the threshold in most rows)."""
+    import torch
+    x = workload(name)
+    cfg, dev = x.cfg, to_dev(x)
+    sh = shape_of(dsa, cfg)
+    R32 = x.R.astype(np.float32)
+    Rd = torch.from_numpy(R32).cuda()
+    print(f"[low precision] {name} bits={bits}", flush=True)
+    packed, codes = {}, {}
+    for which in ("Q", "K"):
+        got, amax = dsa.dsa_project_quantize_bits(sh, bits, dev[which], Rd)
+        torch.cuda.synchronize()
+        want, want_amax = oracle.project_quantize(getattr(x, which), R32, bits=bits)
+        assert float(amax.item()) == float(want_amax)
+        want_packed = oracle.pack_codes(want, bits)
+        assert np.array_equal(got.cpu().numpy(), want_packed.reshape(got.shape)), which
+        packed[which], codes[which] = got, want
+    idx = dsa.dsa_predict_mask_bits(sh, bits, packed["Q"], packed["K"])
+    torch.cuda.synchronize()
+    want_idx = oracle.predict_mask(codes["Q"], codes["K"], cfg.keep, cfg.vec)
+    assert np.array_equal(idx.cpu().numpy().reshape(want_idx.shape), want_idx)
+    # bits = 8 through the same entry points is the int8 path
+    if bits == 4 and name == "C1":
+        p8, _ = dsa.dsa_project_quantize_bits(sh, 8, dev["K"], Rd)
+        assert np.array_equal(p8.cpu().numpy().view(np.int8), oracle.project_quantize(x.K, R32)[0].reshape(p8.shape))
+        i8 = dsa.dsa_predict_mask_bits(sh, 8, dev["Qt"].view(torch.uint8), dev["Kt"].view(torch.uint8))
+        assert np.array_equal(i8.cpu().numpy().reshape(-1, cfg.keep), oracle.predict_mask(x.Qt, x.Kt, cfg.keep, cfg.vec))
+
+
+def test_low_precision_errors(dsa):
+    import torch
+    sh = dsa.make_shape(1, 1, 64, 64, 16, 8, 1, dsa.DSA_F32, 0.125)
+    q = torch.zeros((1, 1, 64, 8), dtype=torch.uint8, device="cuda")
+    with pytest.raises(dsa.DsaError) as e:                                 # bits = 3 is not a storage format
+        dsa.binding._check(dsa.binding.lib().dsa_predict_mask_bits(
+            __import__("ctypes").byref(sh), 3, q.data_ptr(), q.data_ptr(), q.data_ptr(), q.data_ptr(), 1 << 20, None), "bits")
+    assert e.value.status == 3
+    with pytest.raises(dsa.DsaError) as e:                                 # workspace too small for the widened codes
+        dsa.dsa_predict_mask_bits(sh, 4, q, q, ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 5
+
+
 def test_errors_launch_nothing(dsa):
     import torch
     sh = dsa.make_shape(1, 1, 64, 64, 16, 65, 1, dsa.DSA_F32, 0.125)      # keep > L

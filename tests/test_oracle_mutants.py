@@ -31,7 +31,13 @@ MUTANTS = [
     ("list not sorted ascending", "qsort(out, (size_t)keep, sizeof(int32_t), by_int32);", ";"),
     ("keep rounds down", "floor(ratio * (double)L + 0.5)", "floor(ratio * (double)L)"),
     ("codes truncated instead of rounded", "float v = rintf(Y[t] * s);", "float v = truncf(Y[t] * s);"),
-    ("quantiser range 128", "amax > 0.0f ? 127.0f / amax : 0.0f", "amax > 0.0f ? 128.0f / amax : 0.0f"),
+    ("quantiser range 2^(bits-1)", "const float qmax = (float)((1 << (bits - 1)) - 1);",
+     "const float qmax = (float)(1 << (bits - 1));"),
+    ("precision ignored: always the int8 range", "const float qmax = (float)((1 << (bits - 1)) - 1);",
+     "const float qmax = 127.0f;"),
+    ("packed fields in the opposite order", "<< (bits * f);", "<< (bits * (per - 1 - f));"),
+    ("unpacking without sign extension", "codes[j] = (int8_t)(((int32_t)field ^ sign) - sign);",
+     "codes[j] = (int8_t)field; (void)sign;"),
     ("projection matrix transposed", "y = fmaf(X[r * d + c], R[(int64_t)c * k + j], y);",
      "y = fmaf(X[r * d + c], R[(int64_t)(j % d) * k + (c % k)], y);"),
 ]

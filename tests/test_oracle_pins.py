@@ -343,3 +343,77 @@ def test_projection_quantiser_against_float64(oracle, workload):
         # and the workload's own codes (float64 R) are the same up to the same kind of step
         d2 = np.abs(codes.astype(np.int32) - want.astype(np.int32))
         assert d2.max() <= 1 and (d2 != 0).mean() < 2e-2
+
+
+# ---------------------------------------------------------------- lower prediction precision (section 3.3, table 2)
+def test_low_precision_quantiser_closed_forms(oracle):
+    # INT4: amax = 7 makes the scale exactly 1, the codes are the projected values, halves go to even
+    X = np.array([[7.0], [-7.0], [0.5], [1.5], [2.5], [-3.5], [6.4], [6.6]], np.float32)
+    R = np.array([[1.0]], np.float32)
+    codes, amax = oracle.project_quantize(X, R, bits=4)
+    assert amax == np.float32(7.0)
+    assert codes[:, 0].tolist() == [7, -7, 0, 2, 2, -4, 6, 7]
+    # INT2: three levels; with amax = 1 the boundaries sit at +-0.5 (halves to even: to 0)
+    X2 = np.array([[1.0], [-1.0], [0.5], [-0.5], [0.51], [-0.51], [0.0]], np.float32)
+    codes2, amax2 = oracle.project_quantize(X2, R, bits=2)
+    assert amax2 == np.float32(1.0)
+    assert codes2[:, 0].tolist() == [1, -1, 0, 0, 1, -1, 0]
+    # the same tensor at 8 bits uses the full int8 range
+    assert oracle.project_quantize(X, R, bits=8)[0][:, 0].tolist() == [127, -127, 9, 27, 45, -64, 116, 120]
+
+
+@pytest.mark.parametrize("bits", [4, 2])
+def test_low_precision_codes_against_float64(oracle, workload, bits):
+    x = workload("C1")
+    qmax = 2 ** (bits - 1) - 1
+    R32 = x.R.astype(np.float32)
+    codes, amax = oracle.project_quantize(x.K, R32, bits=bits)
+    assert codes.min() >= -qmax and codes.max() <= qmax and np.abs(codes).max() == qmax
+    y64 = x.K.astype(np.float64) @ R32.astype(np.float64)
+    ref = np.clip(np.rint(y64 * (qmax / np.abs(y64).max())), -qmax, qmax)
+    diff = np.abs(codes.astype(np.int32) - ref.astype(np.int32))
+    assert diff.max() <= 1 and (diff != 0).mean() < 1e-3
+
+
+def test_code_packing_layout(oracle):
+    # hand-worked bytes: low field first, two's complement fields
+    assert oracle.pack_codes(np.array([[7, -7, 0, 1, -1, 3, -4, 5]], np.int8), 4).tolist() == [[0x97, 0x10, 0x3F, 0x5C]]
+    assert oracle.pack_codes(np.array([[1, -1, 0, 1, 0, 0, -1, -1]], np.int8), 2).tolist() == [[0b01001101, 0b11110000]]
+    assert oracle.pack_codes(np.array([[-5, 100]], np.int8), 8).tolist() == [[251, 100]]
+    # every byte value unpacks to what plain integer arithmetic on its fields gives
+    allb = np.arange(256, dtype=np.uint8).reshape(1, 256)
+    for bits in (4, 2):
+        per, half = 8 // bits, 1 << (bits - 1)
+        got = oracle.unpack_codes(allb, bits).reshape(256, per)
+        for b in range(256):
+            fields = [(b >> (bits * f)) % (1 << bits) for f in range(per)]
+            assert got[b].tolist() == [v - (1 << bits) if v >= half else v for v in fields]
+    # round trip over the whole code range, and a code outside it is refused
+    rng = np.random.default_rng(5)
+    for bits in (4, 2, 8):
+        qmax = 2 ** (bits - 1) - 1
+        c = rng.integers(-qmax, qmax + 1, size=(3, 5, 32)).astype(np.int8)
+        p = oracle.pack_codes(c, bits)
+        assert p.shape == (3, 5, 32 * bits // 8)
+        assert np.array_equal(oracle.unpack_codes(p, bits), c)
+    with pytest.raises(ValueError):
+        oracle.pack_codes(np.array([[8, 0]], np.int8), 4)
+
+
+def test_low_precision_mask_is_the_mask_of_the_codes(oracle, workload):
+    # the predictor sees the integer codes whatever their storage: packing and unpacking changes nothing,
+    # and with so few levels ties are everywhere, so the lower index must win often
+    x = workload("C1")
+    cfg = x.cfg
+    R32 = x.R.astype(np.float32)
+    q4, _ = oracle.project_quantize(x.Q, R32, bits=4)
+    k4, _ = oracle.project_quantize(x.K, R32, bits=4)
+    idx = oracle.predict_mask(q4, k4, cfg.keep, cfg.vec)
+    back = oracle.predict_mask(oracle.unpack_codes(oracle.pack_codes(q4, 4), 4),
+                               oracle.unpack_codes(oracle.pack_codes(k4, 4), 4), cfg.keep, cfg.vec)
+    assert np.array_equal(idx, back)
+    S = oracle.approx_scores(q4, k4, cfg.vec)
+    order = np.argsort(-S, axis=1, kind="stable")[:, :cfg.keep]
+    assert np.array_equal(np.sort(order, axis=1), idx)
+    kth = np.take_along_axis(S, order[:, -1:], axis=1)
+    assert ((S == kth).sum(1) > 1).mean() > 0.5      # most rows have a tie at the threshold
