@@ -357,6 +357,16 @@ __device__ __forceinline__ int kth_largest_of(const int (&v)[NR], int used, int 
     }
 }
 
+// m with all but its r lowest set bits cleared (r <= 0: none kept).
+__device__ __forceinline__ unsigned lowest_set_bits(unsigned m, int r)
+{
+    if (r <= 0) return 0u;
+    if (r >= __popc(m)) return m;
+    unsigned rest = m;
+    for (int i = 0; i < r; ++i) rest &= rest - 1;
+    return m & ~rest;
+}
+
 // (A) for one wavefront and one chunk: scores of TC tiles into registers plus bucket maxima.
 // Key rows are loaded unconditionally from clamped addresses: a key beyond L only feeds output
 // rows that TAIL overwrites with INT32_MIN, and a contraction piece beyond Ka meets a zero unit
@@ -434,12 +444,18 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
     // fall into different LDS banks.
     const int NBTp = NBT + 1, NWp = NW + 1, NHTp = NHT + 1;
     int *T0s = smem;                                                            // [16]
-    int *seg = T0s + kTileUnits;                                                // [16][NHT][HC]
+    int *strict = T0s + kTileUnits;                                             // [16] unit redone with score > T0
+    int *wrapf = strict + kTileUnits;                                           // [16] some holder wrapped
+    int *ncand = wrapf + kTileUnits;                                            // [16][4] candidates (single chunk),
+                                                                                // one counter per lane group
+    int *seg = ncand + 4 * kTileUnits;                                          // [16][NHT][HC]
     unsigned *bitmap = reinterpret_cast<unsigned *>(seg + kTileUnits * SL);     // [16][NW+1]
     int *cnts = reinterpret_cast<int *>(bitmap + kTileUnits * NWp);             // [16][NHT+1]
     int *bm = cnts + kTileUnits * NHTp;                                         // [16][NBT+1], phases A-B
     int2 *compact = reinterpret_cast<int2 *>(bm) + w * kCompactCap;             // per wavefront, phase D:
                                                                                 // reuses the bm storage
+    // [16][NW+1] keys whose score equals T0, single-chunk plans only
+    unsigned *eqmap = reinterpret_cast<unsigned *>(bm + max(kTileUnits * NBTp, W * kCompactCap * 2));
 
     // A workgroup works through tiles blockIdx.x, blockIdx.x + gridDim.x, ...: with one workgroup
     // resident per compute unit the stores of one tile then drain while the next tile's keys load.
@@ -469,7 +485,13 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
     // the key operand repeats from step to step when k divides the step width
     const bool same_kop = (KSTEP % k) == 0;
 
-    if (threadIdx.x < kTileUnits) T0s[threadIdx.x] = kAllCandidates;
+    if (threadIdx.x < kTileUnits) {
+        T0s[threadIdx.x] = kAllCandidates;
+        strict[threadIdx.x] = 0;
+        wrapf[threadIdx.x] = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ncand[4 * threadIdx.x + i] = 0;
+    }
     __syncthreads();
 
     PHASE_START();
@@ -542,40 +564,67 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
         __syncthreads();
         PHASE_MARK(3);
 
-        // (C) candidates: bit j of a unit's bitmap = score(unit, key j) >= T0; passing scores are
-        // appended, in key order, to this holder's segment.
-        const int T0 = T0s[c];
+        // (C) candidates: bit j of a unit's bitmap = score(unit, key j) >= thr; passing scores are
+        // appended, in key order, to this holder's segment.  thr is T0.
+        // (C') Ties.  When a unit's candidates do not fit (more than the compact list holds, or a
+        // holder with HC or more) it is nearly always because very many keys share the score T0, as
+        // with few-level codes.  Such a unit goes through the same code once more with thr = T0 + 1:
+        // bitmap and segments then take score > T0, and the bits that drop out of the bitmap are the
+        // keys with score == T0, kept in a second bitmap.  If fewer than keep scores lie above T0 the
+        // answer is those plus the first ties in key order and needs no score at all.  Only plans
+        // with a single chunk still hold every score in registers at that point.
         const int holder = chunk * 4 * W + 4 * w + g;
         int *myseg = seg + c * SL + (holder << hc_log2);
         // entry o sits in slot (o + rot) % HC; the rotation spreads the lanes of this instruction, and
         // the lanes that later read one unit's segments, over the LDS banks
         const int rot = lane + (holder >> 2);
         unsigned *words = bitmap + c * NWp + out_lo / 32;
-        int pos0 = 0;
+        int thr = T0s[c];
+        bool mine = true;             // this lane's unit takes part in the current pass
+        for (int pass = 0; pass < 2; ++pass) {
+            if (mine) {
+                int pos0 = 0;
 #pragma unroll
-        for (int q = 0; q < WPH; ++q) {
-            unsigned word = 0;
-            int pos = pos0;
+                for (int q = 0; q < WPH; ++q) {
+                    unsigned word = 0;
+                    int pos = pos0;
 #pragma unroll
-            for (int e = 0; e < 32; ++e) {
-                const int s = acc[8 * q + e / 4][e % 4];
-                myseg[(pos + rot) & (HC - 1)] = s;      // kept only if the end moves past it
-                // word = 2*word + (s >= T0): compare into the carry, add with carry
-                asm("v_cmp_ge_i32 vcc, %1, %2\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc"
-                    : "+v"(word)
-                    : "v"(s), "v"(T0)
-                    : "vcc");
-                pos = pos0 + __popc(word);
+                    for (int e = 0; e < 32; ++e) {
+                        const int s = acc[8 * q + e / 4][e % 4];
+                        myseg[(pos + rot) & (HC - 1)] = s;      // kept only if the end moves past it
+                        // word = 2*word + (s >= thr): compare into the carry, add with carry
+                        asm("v_cmp_ge_i32 vcc, %1, %2\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc"
+                            : "+v"(word)
+                            : "v"(s), "v"(thr)
+                            : "vcc");
+                        pos = pos0 + __popc(word);
+                    }
+                    word = __brev(word);                // the first key of the word was shifted in first
+                    if (pass) eqmap[c * NWp + out_lo / 32 + q] = words[q] & ~word;
+                    words[q] = word;
+                    pos0 = pos;
+                }
+                cnts[c * NHTp + holder] = pos0;         // HC or more means the segment wrapped
+                if (pass == 0 && nchunks == 1 && thr != kAllCandidates) {
+                    atomicAdd(&ncand[4 * c + g], pos0);     // 64 different addresses per instruction
+                    if (pos0 >= HC) wrapf[c] = 1;
+                }
             }
-            words[q] = __brev(word);            // the first key of the word was shifted in first
-            pos0 = pos;
+            PHASE_MARK(4);
+            if (nchunks != 1) break;
+            __syncthreads();              // also the barrier in front of (D)
+            if (pass) break;
+            const int4 part = *reinterpret_cast<const int4 *>(ncand + 4 * c);
+            mine = (part.x + part.y) + (part.z + part.w) > kCompactCap || wrapf[c] != 0;
+            // lanes c = 0..15 of every wavefront see all units: the same outcome everywhere
+            if (__ballot(mine) == 0) break;
+            strict[c] = mine;
+            thr += 1;
         }
-        cnts[c * NHTp + holder] = pos0;         // HC or more means the segment wrapped
-        PHASE_MARK(4);
         // bm / T0s are rewritten only after the next chunk's first barrier
     }
     if (DSA_PREDICT_STOP >= 1 && DSA_PREDICT_STOP <= 3) { __syncthreads(); continue; }
-    __syncthreads();
+    if (nchunks != 1) __syncthreads();
     PHASE_MARK(5);
 
     // (D) exact selection among the candidates, one wavefront per unit
@@ -589,7 +638,8 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
         const int *sg = seg + uu * SL;
         const int *qu = reinterpret_cast<const int *>(Qh + (size_t)u * Ka);
         int32_t *out = idx + ((size_t)n * G + u) * keep;
-        const int T0 = T0s[uu];
+        // candidates have score >= lo0: T0, or T0 + 1 for a unit redone with the strict threshold
+        const int lo0 = T0s[uu] + strict[uu];
 
         int nc = 0;
         for (int h = lane; h < NHT; h += kWave) nc += cu[h];
@@ -598,7 +648,39 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
         PHASE_COUNT(12, nc);
         PHASE_COUNT(13, 1);
 
-        if (fits) {
+        if (strict[uu] && nc < keep) {
+            // fewer than keep scores above T0 and at least keep at or above it: the keep-th largest is
+            // T0, and the answer is every key above it plus the first keep - nc keys equal to it
+            const unsigned *ew = eqmap + uu * NWp;
+            int need = keep - nc, out_base = 0;
+            for (int w0 = 0; w0 < NW; w0 += 2 * kWave) {
+                const int wi = w0 + 2 * lane;
+                const bool live = wi < NW;
+                const int wic = min(wi, NW - 2);
+                const unsigned g0 = live ? bw[wic] : 0u, g1 = live ? bw[wic + 1] : 0u;
+                const unsigned e0 = live ? ew[wic] : 0u, e1 = live ? ew[wic + 1] : 0u;
+                const int ce0 = __popc(e0), ce = ce0 + __popc(e1);
+                int ties_round;
+                const int ties_incl = wave_incl_scan(ce, lane, &ties_round);
+                const int room = need - (ties_incl - ce);        // ties this lane may still take
+                need -= ties_round;
+                const unsigned s0 = g0 | lowest_set_bits(e0, room);
+                const unsigned s1 = g1 | lowest_set_bits(e1, room - ce0);
+                const int cs = __popc(s0) + __popc(s1);
+                int sel_round;
+                const int sel_incl = wave_incl_scan(cs, lane, &sel_round);
+                int32_t *dst = out + out_base + sel_incl - cs;
+                out_base += sel_round;
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    unsigned m = half ? s1 : s0;
+                    while (m) {
+                        *dst++ = (wic + half) * 32 + __ffs(m) - 1;
+                        m &= m - 1;
+                    }
+                }
+            }
+        } else if (fits) {
             // candidates in key order as (score, key) pairs; a lane takes two bitmap words per round
             int rank_base = 0;
             for (int w0 = 0; w0 < NW; w0 += 2 * kWave) {
@@ -685,7 +767,7 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
             }
             PHASE_MARK(7);
             // every candidate reaches T0 and there are at least keep of them
-            const int T = kth_largest_of<NR>(sc, groups, keep, T0, wave_max(hi));
+            const int T = kth_largest_of<NR>(sc, groups, keep, lo0, wave_max(hi));
             PHASE_MARK(8);
             if (DSA_PREDICT_STOP == 5) { if (lane == 0) out[0] = T; continue; }
             int gt = 0;
@@ -719,7 +801,7 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
             int hi = INT32_MIN;
             for (int j = lane; j < L; j += kWave) hi = max(hi, flagged_score(j));
             hi = wave_max(hi);
-            int lo = T0;
+            int lo = lo0;
             while (lo < hi) {
                 const int mid = (int)(lo + ((long long)hi - lo + 1) / 2);
                 int ge = 0;
@@ -783,9 +865,10 @@ TilePlan plan_tiles(const dsa_shape &sh)
     auto lds_bytes = [&](int nb, int hcl) {
         const size_t bm_bytes = sizeof(int) * (size_t)kTileUnits * (4 * p.W * nb + 1);
         const size_t compact_bytes = sizeof(int2) * (size_t)p.W * kCompactCap;      // shares bm's storage
-        return sizeof(int) * (kTileUnits + kTileUnits * (NW + 1) + ((size_t)kTileUnits * NHT << hcl) +
+        const size_t eq_bytes = p.nchunks == 1 ? sizeof(int) * kTileUnits * (NW + 1) : 0;   // ties bitmap
+        return sizeof(int) * (7 * kTileUnits + kTileUnits * (NW + 1) + ((size_t)kTileUnits * NHT << hcl) +
                               (size_t)kTileUnits * (NHT + 1)) +
-               (bm_bytes > compact_bytes ? bm_bytes : compact_bytes);
+               (bm_bytes > compact_bytes ? bm_bytes : compact_bytes) + eq_bytes;
     };
     while (lds_bytes(p.NB, p.hc_log2) > kLdsBudget && (p.NB > 8 || p.hc_log2 > 0)) {
         if (p.NB > 8) p.NB /= 2; else --p.hc_log2;
