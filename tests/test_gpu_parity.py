@@ -142,6 +142,33 @@ def test_mask_with_heavy_ties(dsa, oracle, vec, lo, hi):
         assert np.array_equal(idx.cpu().numpy().reshape(want.shape), want)
 
 
+@pytest.mark.parametrize("L", [4096, 2500])
+def test_mask_with_score_plateaus(dsa, oracle, L):
+    """Scores that take three values only, on plateaus of several hundred keys: the kept set is
+    decided inside a plateau (all ties), at its edge, or needs more candidates than the fast
+    selection holds -- the strict-threshold pass, the ties-only answer and the recomputing path."""
+    import torch
+    B, H, k = 1, 2, 32
+    rng = np.random.Generator(np.random.Philox(77 + L))
+    Kt = np.zeros((B, H, L, k), np.int8)
+    level = rng.permutation(L)
+    Kt[:, :, level[:600], 0] = 2           # 600 keys score 2 * q0, 600 keys score q0, the rest 0
+    Kt[:, :, level[600:1200], 0] = 1
+    Qt = np.zeros((B, H, L, k), np.int8)
+    Qt[..., 0] = rng.integers(-3, 4, size=(B, H, L))     # negative q0 reverses the order, 0 ties everything
+    for vec in (1, 8):
+        for keep in (1, 300, 600, 601, 700, 1200, 1300, L):
+            sh = dsa.make_shape(B, H, L if vec == 1 else L - L % 8, 64, k, keep, vec, dsa.DSA_F32, 0.125)
+            Lv = sh.L
+            q, kk = np.ascontiguousarray(Qt[:, :, :Lv]), np.ascontiguousarray(Kt[:, :, :Lv])
+            if keep > Lv:
+                continue
+            print(f"[plateaus] L={Lv} vec={vec} keep={keep}", flush=True)
+            idx = dsa.dsa_predict_mask(sh, torch.from_numpy(q).cuda(), torch.from_numpy(kk).cuda())
+            want = oracle.predict_mask(q, kk, keep, vec)
+            assert np.array_equal(idx.cpu().numpy().reshape(want.shape), want)
+
+
 def test_reproducible_and_stream_ordered(dsa, oracle, workload):
     """Same inputs, same bits; and the path runs on whatever stream the caller makes current."""
     import torch
