@@ -471,17 +471,22 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
     const int8_t *Kh = Kt + (size_t)n * L * k;
     const int8_t *Qh = Qt + (size_t)n * L * k;   // unit u occupies bytes [u*Ka, u*Ka + Ka)
 
-    // B operand: unit u0+c, piece g of every contraction step.  Key operand offsets per step.
+    // B operand: unit u0+c, piece g of every contraction step.  Key operand offsets per step.  The
+    // 16-wavefront plans (128 registers a lane) load them per chunk, so that the registers are free
+    // again in the selection phases; the 8-wavefront plans keep them.
     typename M::op_t qop[MAXSTEPS];
     int koff[MAXSTEPS];
-    const bool unit_live = u0 + c < G;
+    auto load_unit_operands = [&]() {
+        const bool unit_live = u0 + c < G;
 #pragma unroll
-    for (int s = 0; s < MAXSTEPS; ++s) {
-        const int m = KSTEP * s + M::kBytes * g;
-        const bool ok = s < nsteps && m < Ka;
-        qop[s] = (ok && unit_live) ? M::load(Qh + (size_t)(u0 + c) * Ka + m) : M::zero();
-        koff[s] = ok ? m % k : 0;
-    }
+        for (int s = 0; s < MAXSTEPS; ++s) {
+            const int m = KSTEP * s + M::kBytes * g;
+            const bool ok = s < nsteps && m < Ka;
+            qop[s] = (ok && unit_live) ? M::load(Qh + (size_t)(u0 + c) * Ka + m) : M::zero();
+            koff[s] = ok ? m % k : 0;
+        }
+    };
+    if (MAXW != 16) load_unit_operands();
     // the key operand repeats from step to step when k divides the step width
     const bool same_kop = (KSTEP % k) == 0;
 
@@ -500,6 +505,7 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
         const int wave_lo = chunk_base + w * kTileUnits * TC;          // first key of this wavefront
         const int out_lo = wave_lo + g * 4 * TC;                        // first key of this lane's stream
         const int op_lo = wave_lo + (c >> 2) * 4 * TC + (c & 3);        // operand row c of tile 0
+        if (MAXW == 16) load_unit_operands();
         v4i acc[TC];
         int bmax[NB];
 #pragma unroll
