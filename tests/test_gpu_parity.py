@@ -326,6 +326,27 @@ def test_low_precision_prediction(dsa, oracle, workload, name, bits):
         assert np.array_equal(i8.cpu().numpy().reshape(-1, cfg.keep), oracle.predict_mask(x.Qt, x.Kt, cfg.keep, cfg.vec))
 
 
+@pytest.mark.parametrize("bits", [4, 2])
+def test_low_precision_ragged(dsa, oracle, bits):
+    """Packed codes on shapes with a ragged tail, the smallest and the largest k, both granularities."""
+    import torch
+    for (L, k, vec, keep) in [(8, 16, 8, 1), (77, 16, 1, 5), (1000, 128, 8, 40), (4104, 48, 8, 200), (6000, 32, 1, 300)]:
+        cfg = di.custom_config(B=1, H=2, L=L, d=64, dtype="f32", rank=4, k=k, keep=keep, vec=vec, seed=L + bits)
+        x = di.make_inputs(cfg)
+        sh = shape_of(dsa, cfg)
+        R32 = x.R.astype(np.float32)
+        print(f"[low precision ragged] L={L} k={k} vec={vec} keep={keep} bits={bits}", flush=True)
+        q, _ = oracle.project_quantize(x.Q, R32, bits=bits)
+        kk, _ = oracle.project_quantize(x.K, R32, bits=bits)
+        qp = torch.from_numpy(oracle.pack_codes(q, bits)).cuda()
+        kp = torch.from_numpy(oracle.pack_codes(kk, bits)).cuda()
+        idx = dsa.dsa_predict_mask_bits(sh, bits, qp, kp)
+        want = oracle.predict_mask(q, kk, keep, vec)
+        assert np.array_equal(idx.cpu().numpy().reshape(want.shape), want)
+        got, _ = dsa.dsa_project_quantize_bits(sh, bits, to_dev(x)["K"], torch.from_numpy(R32).cuda())
+        assert np.array_equal(got.cpu().numpy(), oracle.pack_codes(kk, bits).reshape(got.shape))
+
+
 def test_low_precision_errors(dsa):
     import torch
     sh = dsa.make_shape(1, 1, 64, 64, 16, 8, 1, dsa.DSA_F32, 0.125)
