@@ -621,7 +621,7 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
             __syncthreads();              // also the barrier in front of (D)
             if (pass) break;
             const int4 part = *reinterpret_cast<const int4 *>(ncand + 4 * c);
-            mine = (part.x + part.y) + (part.z + part.w) > kCompactCap || wrapf[c] != 0;
+            mine = ((part.x + part.y) + (part.z + part.w) > kCompactCap || wrapf[c] != 0) && u0 + c < G;
             // lanes c = 0..15 of every wavefront see all units: the same outcome everywhere
             if (__ballot(mine) == 0) break;
             strict[c] = mine;
@@ -884,6 +884,35 @@ TilePlan plan_tiles(const dsa_shape &sh)
     return p;
 }
 
+// Workgroups to launch when each is to loop over tiles: the number of compute units if a compute
+// unit holds exactly one workgroup of this kernel (nothing else hides the start and the end of a
+// tile then), rounded down to a multiple of the XCD count; 0 when several fit (the hardware
+// already overlaps them) and the launch should be one workgroup per tile.  The answer is kept per
+// (kernel, block size, LDS size, device) and thread: the occupancy query costs microseconds that
+// a launch-bound call would feel.
+hipError_t looping_grid(const void *kern, int threads, size_t lds, unsigned *out)
+{
+    struct Entry { const void *kern; int threads; size_t lds; int dev; unsigned grid; };
+    static thread_local Entry cache[8];
+    static thread_local int used = 0;
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev)) return e;
+    for (int i = 0; i < used; ++i)
+        if (cache[i].kern == kern && cache[i].threads == threads && cache[i].lds == lds && cache[i].dev == dev) {
+            *out = cache[i].grid;
+            return hipSuccess;
+        }
+    int cus = 0, per_cu = 0;
+    if (hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) return e;
+    if (hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, threads, lds)) return e;
+    unsigned grid = per_cu == 1 && cus > 0 ? (unsigned)cus : 0u;
+    grid -= grid % kXcds;
+    const int slot = used < 8 ? used++ : 7;
+    cache[slot] = Entry{kern, threads, lds, dev, grid};
+    *out = grid;
+    return hipSuccess;
+}
+
 template <int TC, int NB, int KSTEP, int MAXSTEPS, int MAXW>
 hipError_t launch_tiles_t(const TilePlan &p, const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt,
                           int32_t *idx, hipStream_t st)
@@ -896,16 +925,8 @@ hipError_t launch_tiles_t(const TilePlan &p, const dsa_shape &sh, const int8_t *
     }
     const unsigned tiles = (unsigned)sh.B * sh.H * p.tiles_per_head;
     // one workgroup per compute unit (a multiple of the XCD count), each looping over tiles
-    int dev = 0, cus = 0, per_cu = 0;
-    if (hipError_t e = hipGetDevice(&dev)) return e;
-    if (hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) return e;
-    if (hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kern),
-                                                                    p.W * kWave, p.lds))
-        return e;
-    // Looping pays when a compute unit holds a single workgroup (nothing else hides the start and the
-    // end of a tile); with several resident workgroups the hardware already overlaps them.
-    unsigned resident = per_cu == 1 ? (unsigned)(cus > 0 ? cus : 0) : 0u;
-    resident -= resident % kXcds;
+    unsigned resident = 0;
+    if (hipError_t e = looping_grid(reinterpret_cast<const void *>(kern), p.W * kWave, p.lds, &resident)) return e;
     const unsigned grid = (resident == 0 || tiles <= resident) ? tiles : resident;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(p.W * kWave), p.lds, st, Qt, Kt, idx, sh.L, sh.k, sh.keep,
                        sh.vec, p.nchunks, p.tiles_per_head, p.hc_log2, tiles);
