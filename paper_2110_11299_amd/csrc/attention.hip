@@ -112,6 +112,15 @@ __device__ __forceinline__ float wave_all_max(float x)
     return x;
 }
 
+// Makes LDS writes of some lanes of a wavefront visible to reads of its other lanes.  Every LDS
+// region below belongs to one wavefront, so no workgroup barrier is ever needed.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // MODE kFused: Q,K,V,idx -> O.  kSddmm: Q,K,idx -> S.  kSpmm: Pin,V,idx -> O.
 template <typename T, int D, int MODE>
 __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
@@ -139,7 +148,7 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
     int *sl = reinterpret_cast<int *>(lds_scores) + wave * (MODE == kFused ? 2 : 1) * keep;
     float *sc = reinterpret_cast<float *>(sl + keep);
     for (int t = lane; t < keep; t += kWave) sl[t] = min(max(list[t], 0), L - 1);
-    __syncthreads();
+    wave_lds_fence();
 #ifndef DSA_ATTN_U
 #define DSA_ATTN_U 4
 #endif
@@ -171,11 +180,11 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
         }
         if (MODE == kSddmm) return;
         m = groups_max<LPR>(m);
-        __syncthreads();
+        wave_lds_fence();
         // unnormalised weights, computed once per kept key (the lanes that share a value row would
         // otherwise each repeat the exponential)
         for (int t = lane; t < keep; t += kWave) sc[t] = __expf(sc[t] - m);
-        __syncthreads();
+        wave_lds_fence();
     }
 
     float o[E], z = 0.f;
@@ -236,12 +245,6 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int kGroupWaves = 4;
 
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
 
 // (The launch bound is twice the launched size: with at most 256 registers per lane the compiler
 // gives the matrix core plain VGPR destinations instead of accumulation registers that every
