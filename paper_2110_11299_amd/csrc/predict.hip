@@ -164,8 +164,14 @@ __global__ __launch_bounds__(kUnitThreads) void predict_unit(const int8_t *__res
 //  (D) one wavefront per unit walks the bitmap in key order, pairs each candidate key with its
 //      score from the segments, bisects for the exact threshold in registers and writes the kept
 //      keys in ascending order, breaking ties by key index through ballot prefix counts.
-// A unit whose candidates do not fit (massive ties, very large keep) takes a slower path that
+// A unit whose candidates do not fit is almost always one where very many keys share the score
+// T0 (codes with few levels).  In a single-chunk plan its lanes run (C) once more with T0 + 1:
+// the bits that drop out of the bitmap are the ties, and if fewer than keep scores lie above T0
+// the answer is those keys plus the first ties in key order, with no score involved.  What still
+// does not fit (very large keep, plateaus above T0, multi-chunk plans) takes a slower path that
 // recomputes scores from Q~, K~ with packed dot products.
+// When a compute unit holds one workgroup, one workgroup per compute unit is launched and each
+// loops over its tiles.
 // ---------------------------------------------------------------------------------------------
 constexpr int kTileUnits = 16;
 
