@@ -14,6 +14,21 @@ import torch
 import dsa_inputs as di
 
 
+def paper_values():
+    """tests/golden/paper_values.txt: `name = value  # citation` lines -> dict of floats."""
+    from pathlib import Path
+    out = {}
+    for line in (Path(__file__).parent / "golden" / "paper_values.txt").read_text().splitlines():
+        line = line.split("#")[0].strip()
+        if line:
+            name, value = (t.strip() for t in line.split("="))
+            out[name] = float(value)
+    return out
+
+
+PAPER = paper_values()
+
+
 def tiny(seed, N=2, L=24, d=8, k=8, lo=-127, hi=127):
     rng = np.random.default_rng(seed)
     Q = rng.standard_normal((N, L, d)).astype(np.float32)
@@ -43,7 +58,12 @@ def python_topk(scores_row, keep):
 def test_keep_from_ratio_matches_counts_the_workloads_print(oracle):
     for cfg in di.CONFIGS.values():
         assert oracle.keep_from_ratio(cfg.L, cfg.ratio) == cfg.keep, cfg.name
-    assert oracle.keep_from_ratio(2000, 0.10) == 200      # DSA-90% at l = 2000 (section 4.3)
+    # the paper's worked example (section 4.3): DSA-90 on a row of length 2000 keeps 200 positions
+    assert oracle.keep_from_ratio(int(PAPER["example_length"]), 1.0 - PAPER["example_sparsity"]) \
+        == int(PAPER["example_kept_per_row"])
+    c4 = di.CONFIGS["C4f"]          # the long-sequence workload takes the paper's profiling shape (section 5.1)
+    assert (c4.H, c4.L, c4.d) == (int(PAPER["profiling_heads"]), int(PAPER["profiling_length"]),
+                                  int(PAPER["profiling_head_dim"]))
     assert oracle.keep_from_ratio(100, 0.0) == 1           # clamped below
     assert oracle.keep_from_ratio(100, 2.0) == 100         # clamped above
     assert oracle.keep_from_ratio(10, 0.25) == 3           # 2.5 rounds up
@@ -173,7 +193,7 @@ def test_sparse_result_equals_additive_mask_form(oracle, vec):
         for i in range(32):
             M[n, i, idx[n * (32 // vec) + i // vec]] = 1.0
     S = np.einsum("nic,njc->nij", Q.astype(np.float64), K.astype(np.float64)) * float(scale)
-    Sm = S - 1e4 * (1.0 - M)
+    Sm = S - PAPER["mask_constant"] * (1.0 - M)
     E = np.exp(Sm - Sm.max(axis=-1, keepdims=True))
     A = E / E.sum(axis=-1, keepdims=True)
     assert (A[M == 0] == 0).all()                       # masked weights vanish exactly
