@@ -242,6 +242,7 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
 // budget of bfloat16 inputs); scores, softmax statistics and accumulation are fp32.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 constexpr int kGroupWaves = 4;
 
@@ -263,9 +264,10 @@ __global__ __launch_bounds__(2 * kGroupWaves *kWave) void attention_groups_bf16(
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int c = lane & 15, g = lane >> 4;
-    const size_t per_wave = (size_t)8 * keep_pad * sizeof(float) + 32 * VROW;
+    const size_t per_wave = (size_t)9 * keep_pad * sizeof(float) + 32 * VROW;
     float *sS = reinterpret_cast<float *>(lds_raw + wave * per_wave);          // [8][keep_pad]
-    char *sV = reinterpret_cast<char *>(sS + 8 * keep_pad);                    // [32][VROW]
+    int *sl = reinterpret_cast<int *>(sS + 8 * keep_pad);                      // [keep_pad] key list
+    char *sV = reinterpret_cast<char *>(sl + keep_pad);                        // [32][VROW]
 
     const unsigned vblock = xcd_contiguous(blockIdx.x, gridDim.x);
     const unsigned grp = vblock * kGroupWaves + wave;
@@ -283,23 +285,44 @@ __global__ __launch_bounds__(2 * kGroupWaves *kWave) void attention_groups_bf16(
         qop[s] = __builtin_bit_cast(bf16x8, raw);
     }
 
-    // scores of all kept keys -> LDS, running maximum per query
+    // the group's key list once into LDS, clamped into [0, L) (no idx can send a gather outside K / V)
+    // and padded with its last entry
+    for (int t = lane; t < keep_pad; t += kWave) sl[t] = min(max(list[min(t, keep - 1)], 0), L - 1);
+    wave_lds_fence();
+
+    // scores of all kept keys -> LDS, running maximum per query.  A ring of PF tiles of key rows is
+    // kept in flight: the rows of tile t + PF are requested as soon as tile t has been consumed.
     float mx = -INFINITY;
-    for (int t0 = 0; t0 < keep_pad; t0 += 16) {
-        const int j = min(max(list[min(t0 + c, keep - 1)], 0), L - 1);
-        const uint16_t *krow = Kh + (size_t)j * D + 8 * g;
-        v4f acc = {0.f, 0.f, 0.f, 0.f};
+    constexpr int PF = 1;          // deeper rings measured no faster
+    bf16x8 kring[PF][KS];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const bf16x8 kop = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(krow + 32 * s));
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qop[s], acc, 0, 0, 0);
-        }
+    for (int p = 0; p < PF; ++p) {
+        const uint16_t *krow = Kh + (size_t)sl[min(16 * p, keep_pad - 16) + c] * D + 8 * g;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            acc[i] = t0 + 4 * g + i < keep ? acc[i] * scale : -INFINITY;
-            mx = fmaxf(mx, acc[i]);
+        for (int s = 0; s < KS; ++s)
+            kring[p][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const v4u *>(krow + 32 * s));
+    }
+    for (int t0 = 0; t0 < keep_pad; t0 += 16 * PF) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const int tile = t0 + 16 * p;
+            if (tile < keep_pad) {
+                v4f acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kring[p][s], qop[s], acc, 0, 0, 0);
+                const uint16_t *krow = Kh + (size_t)sl[min(tile + 16 * PF, keep_pad - 16) + c] * D + 8 * g;
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    kring[p][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const v4u *>(krow + 32 * s));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    acc[i] = tile + 4 * g + i < keep ? acc[i] * scale : -INFINITY;
+                    mx = fmaxf(mx, acc[i]);
+                }
+                if (c < 8) *reinterpret_cast<v4f *>(sS + c * keep_pad + tile + 4 * g) = acc;
+            }
         }
-        if (c < 8) *reinterpret_cast<v4f *>(sS + c * keep_pad + t0 + 4 * g) = acc;
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
     mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
@@ -310,39 +333,57 @@ __global__ __launch_bounds__(2 * kGroupWaves *kWave) void attention_groups_bf16(
     for (int ct = 0; ct < CT; ++ct) o[ct] = v4f{0.f, 0.f, 0.f, 0.f};
     float z = 0.f;
     const float *srow = sS + (c & 7) * keep_pad + 4 * g;
-    for (int t0 = 0; t0 < keep_pad; t0 += 32) {
-        // 32 gathered value rows -> LDS
+    // value rows of a step: 32 / RPI pieces of 16 bytes per lane; a ring of VF steps is kept in flight
+    constexpr int VP = 32 / RPI;
+    constexpr int VF = 1;
+    const int vrow = lane / LPR, vpiece = lane % LPR;
+    v4u vring[VF][VP];
 #pragma unroll
-        for (int rr = 0; rr < 32 / RPI; ++rr) {
-            const int row = rr * RPI + lane / LPR, piece = lane % LPR;
-            const int j = min(max(list[min(t0 + row, keep - 1)], 0), L - 1);
-            const uint4 raw = *reinterpret_cast<const uint4 *>(Vh + (size_t)j * D + piece * 8);
-            *reinterpret_cast<uint4 *>(sV + row * VROW + piece * 16) = raw;
-        }
-        // weights of this lane's 8 slots
-        const v4f s0 = *reinterpret_cast<const v4f *>(srow + t0);
-        const v4f s1 = *reinterpret_cast<const v4f *>(srow + t0 + 16);
-        bf16x8 pa;
+    for (int f = 0; f < VF; ++f)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float p0 = __expf(s0[i] - mx), p1 = __expf(s1[i] - mx);
-            z += p0 + p1;
-            pa[i] = (__bf16)p0;
-            pa[4 + i] = (__bf16)p1;
-        }
-        wave_lds_fence();
+        for (int rr = 0; rr < VP; ++rr)
+            vring[f][rr] = *reinterpret_cast<const v4u *>(
+                Vh + (size_t)sl[min(32 * f, keep_pad - 32) + rr * RPI + vrow] * D + vpiece * 8);
+    for (int t1 = 0; t1 < keep_pad; t1 += 32 * VF) {
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-            bf16x8 vb;
-            const char *col = sV + (16 * ct + c) * 2;
+        for (int f = 0; f < VF; ++f) {
+            const int t0 = t1 + 32 * f;
+            if (t0 < keep_pad) {
+                // 32 gathered value rows -> LDS, and the request for the rows of step t0 + VF
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                vb[i] = *reinterpret_cast<const __bf16 *>(col + (4 * g + i) * VROW);
-                vb[4 + i] = *reinterpret_cast<const __bf16 *>(col + (16 + 4 * g + i) * VROW);
+                for (int rr = 0; rr < VP; ++rr)
+                    *reinterpret_cast<v4u *>(sV + (rr * RPI + vrow) * VROW + vpiece * 16) = vring[f][rr];
+                const int tn = min(t0 + 32 * VF, keep_pad - 32);
+#pragma unroll
+                for (int rr = 0; rr < VP; ++rr)
+                    vring[f][rr] = *reinterpret_cast<const v4u *>(
+                        Vh + (size_t)sl[tn + rr * RPI + vrow] * D + vpiece * 8);
+                // weights of this lane's 8 slots
+                const v4f s0 = *reinterpret_cast<const v4f *>(srow + t0);
+                const v4f s1 = *reinterpret_cast<const v4f *>(srow + t0 + 16);
+                bf16x8 pa;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float p0 = __expf(s0[i] - mx), p1 = __expf(s1[i] - mx);
+                    z += p0 + p1;
+                    pa[i] = (__bf16)p0;
+                    pa[4 + i] = (__bf16)p1;
+                }
+                wave_lds_fence();
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    bf16x8 vb;
+                    const char *col = sV + (16 * ct + c) * 2;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        vb[i] = *reinterpret_cast<const __bf16 *>(col + (4 * g + i) * VROW);
+                        vb[4 + i] = *reinterpret_cast<const __bf16 *>(col + (16 + 4 * g + i) * VROW);
+                    }
+                    o[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, vb, o[ct], 0, 0, 0);
+                }
+                wave_lds_fence();       // the next step overwrites the value tile
             }
-            o[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, vb, o[ct], 0, 0, 0);
         }
-        wave_lds_fence();       // the next step overwrites the value tile
     }
     z += __shfl_xor(z, 16, kWave);
     z += __shfl_xor(z, 32, kWave);
@@ -423,7 +464,7 @@ hipError_t launch_rows(AttnMode mode, const dsa_shape &sh, const void *Q, const 
 size_t groups_lds_bytes(const dsa_shape &sh)
 {
     const size_t keep_pad = (size_t)(sh.keep + 31) / 32 * 32;
-    return kGroupWaves * (8 * keep_pad * sizeof(float) + 32 * ((size_t)sh.d * 2 + 16));
+    return kGroupWaves * (9 * keep_pad * sizeof(float) + 32 * ((size_t)sh.d * 2 + 16));
 }
 
 template <int D>
