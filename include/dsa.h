@@ -21,7 +21,8 @@
  *    instance, by PyTorch).  The library allocates nothing, frees nothing and never
  *    synchronises: kernels are enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *    the default stream) and the call returns.  Inputs are only read, outputs are fully
- *    overwritten, there is no state between calls.  Pointers must be 16-byte aligned.
+ *    overwritten, and no call depends on an earlier one (the library only remembers launch
+ *    parameters it has derived for a device).  Pointers must be 16-byte aligned.
  *  - Tensors are contiguous, innermost dimension last:
  *        Q, K, V   [B, H, L, d]   float (DSA_F32) or bfloat16 bit patterns (DSA_BF16)
  *        Qt, Kt    [B, H, L, k]   int8, the quantised projections Q~, K~
