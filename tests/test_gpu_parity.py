@@ -169,6 +169,44 @@ def test_mask_with_score_plateaus(dsa, oracle, L):
             assert np.array_equal(idx.cpu().numpy().reshape(want.shape), want)
 
 
+@pytest.mark.parametrize("k,vec,keep", [(16, 1, 100), (32, 8, 1638)])
+def test_predictor_at_maximum_length(dsa, oracle, k, vec, keep):
+    """L = 32768, the longest sequence the predictor takes: sampled units against the oracle one by
+    one, every list ascending and in range."""
+    import torch
+    L = 32768
+    Qt, Kt = di.random_int8_case(L + vec, 1, 1, L, k)
+    sh = dsa.make_shape(1, 1, L, 64, k, keep, vec, dsa.DSA_F32, 0.125)
+    print(f"[max L] k={k} vec={vec} keep={keep}", flush=True)
+    idx = dsa.dsa_predict_mask(sh, torch.from_numpy(Qt).cuda(), torch.from_numpy(Kt).cuda())
+    full = idx.cpu().numpy().reshape(-1, keep)
+    assert (np.diff(full, axis=1) > 0).all() and full.min() >= 0 and full.max() < L
+    units = np.arange(0, L // vec, 97)
+    assert np.array_equal(full[units], oracle.predict_mask(Qt, Kt, keep, vec, units=units))
+
+
+def test_attention_at_maximum_keep(dsa, oracle):
+    """keep = 4096, the longest list the attention kernels take (here every key of L = 4096: the
+    result is dense attention), fp32 and bf16, sampled rows against the oracle."""
+    import torch
+    for dtype in ("f32", "bf16"):
+        cfg = di.custom_config(B=1, H=1, L=4096, d=64, dtype=dtype, rank=8, k=16, keep=4096, seed=4096)
+        x = di.make_inputs(cfg)
+        sh = shape_of(dsa, cfg)
+        dev = to_dev(x)
+        print(f"[max keep] {dtype}", flush=True)
+        idx = np.tile(np.arange(4096, dtype=np.int32), (4096, 1))
+        O = dsa.dsa_masked_attention(sh, dev["Q"], dev["K"], dev["V"], torch.from_numpy(idx).cuda().view(1, 1, 4096, 4096))
+        rows = np.arange(0, 4096, 61)
+        want = oracle.masked_attention(x.Q, x.K, x.V, idx, cfg.scale, 1, rows=rows)
+        assert float(np.abs(O.cpu().numpy().reshape(4096, 64)[rows] - want).max()) <= TOL[dtype]
+    sh = dsa.make_shape(1, 1, 8192, 64, 16, 4097, 1, dsa.DSA_F32, 0.125)       # one more is refused
+    z = torch.zeros((1, 1, 8192, 64), device="cuda")
+    with pytest.raises(dsa.DsaError) as e:
+        dsa.dsa_masked_attention(sh, z, z, z, torch.zeros((1, 1, 8192, 4097), dtype=torch.int32, device="cuda"))
+    assert e.value.status == 3
+
+
 def test_reproducible_and_stream_ordered(dsa, oracle, workload):
     """Same inputs, same bits; and the path runs on whatever stream the caller makes current."""
     import torch
