@@ -146,6 +146,12 @@ dsa_status dsa_project_quantize_bits(const dsa_shape *shape, int32_t bits, const
 size_t dsa_predict_workspace_bytes_bits(const dsa_shape *shape, int32_t bits);
 dsa_status dsa_predict_mask_bits(const dsa_shape *shape, int32_t bits, const void *Qt, const void *Kt,
                                  int32_t *idx, void *ws, size_t ws_bytes, void *stream);
+/*   dsa_attention_fwd_bits: the whole path (a)-(c) as dsa_attention_fwd, from packed codes; `ws` holds
+ *     at least dsa_workspace_bytes_bits() (the mask lives there when idx_out is NULL). */
+size_t dsa_workspace_bytes_bits(const dsa_shape *shape, int32_t bits);
+dsa_status dsa_attention_fwd_bits(const dsa_shape *shape, int32_t bits, const void *Q, const void *K,
+                                  const void *V, const void *Qt, const void *Kt, float *O, int32_t *idx_out,
+                                  void *ws, size_t ws_bytes, void *stream);
 
 /* Measurement aid for step (a): runs `blocks` workgroups of 4 wavefronts, each issuing 4*iters
  * independent int8 MFMAs (32x32x32) with no memory traffic, i.e. 4*blocks*4*iters*65536 int8

@@ -21,6 +21,7 @@ EXPORTS = [
     "dsa_spmm", "dsa_masked_attention", "dsa_attention_fwd", "dsa_approx_rowmax", "dsa_mfma_i8_sustained",
     "dsa_project_quantize", "dsa_project_workspace_bytes",
     "dsa_project_quantize_bits", "dsa_predict_workspace_bytes_bits", "dsa_predict_mask_bits",
+    "dsa_workspace_bytes_bits", "dsa_attention_fwd_bits",
     "dsa_status_string", "dsa_version",
 ]
 
@@ -79,6 +80,10 @@ def lib():
         L.dsa_predict_workspace_bytes_bits.argtypes = [shp, i32]
         L.dsa_predict_mask_bits.restype = i32
         L.dsa_predict_mask_bits.argtypes = [shp, i32, vp, vp, vp, vp, sz, vp]
+        L.dsa_workspace_bytes_bits.restype = sz
+        L.dsa_workspace_bytes_bits.argtypes = [shp, i32]
+        L.dsa_attention_fwd_bits.restype = i32
+        L.dsa_attention_fwd_bits.argtypes = [shp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dsa_mfma_i8_sustained.restype = i32
         L.dsa_mfma_i8_sustained.argtypes = [i32, i32, vp, vp]
         L.dsa_status_string.restype = ctypes.c_char_p
@@ -289,3 +294,27 @@ def dsa_predict_mask_bits(shape, bits, Qt, Kt, idx=None, ws=None):
     _check(lib().dsa_predict_mask_bits(ctypes.byref(shape), bits, _ptr(Qt), _ptr(Kt), _ptr(idx), _ptr(ws),
                                        ws.numel(), _stream()), "dsa_predict_mask_bits")
     return idx
+
+
+def workspace_bytes_bits(shape: DsaShape, bits: int) -> int:
+    return int(lib().dsa_workspace_bytes_bits(ctypes.byref(shape), bits))
+
+
+def dsa_attention_fwd_bits(shape, bits, Q, K, V, Qt, Kt, O=None, idx_out=None, ws=None, want_idx=True):
+    """Whole path from packed low-precision codes.  Returns (O, idx or None)."""
+    import torch
+    tq, _, ti, _ = _dims(shape)
+    tp = _packed_dims(shape, bits)
+    dt = _qkv_dtype(shape)
+    _dev(Q, dt, tq); _dev(K, dt, tq); _dev(V, dt, tq); _dev(Qt, torch.uint8, tp); _dev(Kt, torch.uint8, tp)
+    O = torch.empty(tq, dtype=torch.float32, device=Q.device) if O is None else _dev(O, torch.float32, tq)
+    if idx_out is None and want_idx:
+        idx_out = torch.empty(ti, dtype=torch.int32, device=Q.device)
+    elif idx_out is not None:
+        _dev(idx_out, torch.int32, ti)
+    if ws is None:
+        ws = torch.empty(max(workspace_bytes_bits(shape, bits), 16), dtype=torch.uint8, device=Q.device)
+    _check(lib().dsa_attention_fwd_bits(ctypes.byref(shape), bits, _ptr(Q), _ptr(K), _ptr(V), _ptr(Qt), _ptr(Kt),
+                                        _ptr(O), _ptr(idx_out), _ptr(ws), ws.numel(), _stream()),
+           "dsa_attention_fwd_bits")
+    return O, idx_out

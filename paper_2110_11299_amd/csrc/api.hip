@@ -205,6 +205,32 @@ dsa_status dsa_predict_mask_bits(const dsa_shape *sh, int32_t bits, const void *
     return from_hip(dsa::launch_predict(*sh, q8, k8, idx, pws, st));
 }
 
+size_t dsa_workspace_bytes_bits(const dsa_shape *sh, int32_t bits)
+{
+    if (check_predict(sh) != DSA_OK || (bits != 8 && bits != 4 && bits != 2)) return 0;
+    return round_up_256(idx_bytes(*sh)) + dsa_predict_workspace_bytes_bits(sh, bits);
+}
+
+dsa_status dsa_attention_fwd_bits(const dsa_shape *sh, int32_t bits, const void *Q, const void *K, const void *V,
+                                  const void *Qt, const void *Kt, float *O, int32_t *idx_out, void *ws,
+                                  size_t ws_bytes, void *stream)
+{
+    if (!sh || !Q || !K || !V || !Qt || !Kt || !O) return DSA_ERR_NULL;
+    if (bits != 8 && bits != 4 && bits != 2) return DSA_ERR_UNSUPPORTED;
+    if (dsa_status s = check_predict(sh)) return s;
+    if (dsa_status s = check_attention(sh)) return s;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(idx_out) || !aligned16(ws))
+        return DSA_ERR_ALIGN;
+    const size_t mask_bytes = round_up_256(idx_bytes(*sh));
+    const size_t need = (idx_out ? 0 : mask_bytes) + dsa_predict_workspace_bytes_bits(sh, bits);
+    if (need && (!ws || ws_bytes < need)) return DSA_ERR_WORKSPACE;
+    int32_t *idx = idx_out ? idx_out : static_cast<int32_t *>(ws);
+    void *pws = idx_out ? ws : static_cast<void *>(static_cast<char *>(ws) + mask_bytes);
+    if (dsa_status s = dsa_predict_mask_bits(sh, bits, Qt, Kt, idx, pws, ws_bytes - (idx_out ? 0 : mask_bytes), stream))
+        return s;
+    return from_hip(dsa::launch_attention(dsa::kFused, *sh, Q, K, V, idx, nullptr, nullptr, O, (hipStream_t)stream));
+}
+
 dsa_status dsa_mfma_i8_sustained(int32_t blocks, int32_t iters, int32_t *sink, void *stream)
 {
     if (!sink) return DSA_ERR_NULL;

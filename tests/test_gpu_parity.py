@@ -356,6 +356,14 @@ def test_low_precision_prediction(dsa, oracle, workload, name, bits):
     torch.cuda.synchronize()
     want_idx = oracle.predict_mask(codes["Q"], codes["K"], cfg.keep, cfg.vec)
     assert np.array_equal(idx.cpu().numpy().reshape(want_idx.shape), want_idx)
+    # the whole path from the packed codes, with and without the mask handed back
+    O, idx2 = dsa.dsa_attention_fwd_bits(sh, bits, dev["Q"], dev["K"], dev["V"], packed["Q"], packed["K"])
+    O2, none = dsa.dsa_attention_fwd_bits(sh, bits, dev["Q"], dev["K"], dev["V"], packed["Q"], packed["K"], want_idx=False)
+    torch.cuda.synchronize()
+    assert none is None and np.array_equal(idx2.cpu().numpy().reshape(want_idx.shape), want_idx)
+    want_O = oracle.masked_attention(x.Q, x.K, x.V, want_idx, cfg.scale, cfg.vec)
+    assert float(np.abs(O.cpu().numpy().reshape(want_O.shape) - want_O).max()) <= TOL[cfg.dtype]
+    assert torch.equal(O, O2)
     # bits = 8 through the same entry points is the int8 path
     if bits == 4 and name == "C1":
         p8, _ = dsa.dsa_project_quantize_bits(sh, 8, dev["K"], Rd)
