@@ -181,9 +181,12 @@ def main() -> int:
         k_lp, _ = pkg.dsa_project_quantize_bits(sh_f, bits, K, Rd, ws=pws, want_amax=False)
         ws_lp = torch.empty(pkg.binding.predict_workspace_bytes_bits(sh_f, bits), dtype=torch.uint8, device="cuda")
         idx_lp = torch.empty_like(passes[0]["idx"])
+        ws_fwd = torch.empty(pkg.binding.workspace_bytes_bits(sh_f, bits), dtype=torch.uint8, device="cuda")
         low_precision[f"int{bits}"] = dict(
-            predict_ms=timed(lambda: pkg.dsa_predict_mask_bits(sh_f, bits, q_lp, k_lp, idx=idx_lp, ws=ws_lp), reps))
-        del q_lp, k_lp, ws_lp, idx_lp
+            predict_ms=timed(lambda: pkg.dsa_predict_mask_bits(sh_f, bits, q_lp, k_lp, idx=idx_lp, ws=ws_lp), reps),
+            fwd_ms=timed(lambda: pkg.dsa_attention_fwd_bits(sh_f, bits, Q, K, V, q_lp, k_lp, O=passes[0]["O"],
+                                                            idx_out=idx_lp, ws=ws_fwd), reps))
+        del q_lp, k_lp, ws_lp, idx_lp, ws_fwd
     rowmax = torch.empty((cf.B, cf.H, cf.L), dtype=torch.int32, device="cuda")
     contraction_ms = timed(lambda: pkg.dsa_approx_rowmax(sh_f, Qt, Kt, rowmax=rowmax), reps)
 
@@ -274,7 +277,7 @@ def main() -> int:
                            heads_seqs_per_step=heads_seqs, seed=cf.seed),
                roofline=roofline, cpu_baseline=cpu_baseline, stages=stages, contraction=contraction,
                all_configs=all_configs,
-               low_precision_predict=dict(what="dsa_predict_mask_bits at C4 fine-grained (unpack to int8 + int8 path)",
+               low_precision_predict=dict(what="dsa_predict_mask_bits / dsa_attention_fwd_bits at C4 fine-grained (unpack to int8 + int8 path)",
                                           **low_precision),
                project_quantize=dict(what="Q~ and K~ from Q, K and R on the GPU (dsa_project_quantize twice), C4",
                                      ms=project_ms),
