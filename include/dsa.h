@@ -112,6 +112,21 @@ dsa_status dsa_attention_fwd(const dsa_shape *shape, const void *Q, const void *
                              const int8_t *Qt, const int8_t *Kt, float *O, int32_t *idx_out,
                              void *ws, size_t ws_bytes, void *stream);
 
+/* dsa_attention_fwd for callers that cannot allocate device memory and so cannot bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * computation and same kernels as dsa_attention_fwd with idx_out = NULL, but the mask lives in a
+ * fixed array inside the library's device image (dsa_noalloc_max_mask_bytes() = 16 MiB per GPU,
+ * held until the process ends) instead of a caller workspace.  The call allocates and frees
+ * nothing.  The first call on a device resolves the array's address (once per device).
+ * A shape whose mask, B*H*(L/vec)*keep*4 bytes rounded up to 256, exceeds the array returns
+ * DSA_ERR_WORKSPACE and launches nothing.  Every call on one GPU shares that GPU's array: calls
+ * that overlap on one GPU (different streams or threads) race on the mask; calls on one stream
+ * are ordered and safe.  Nothing in the array has to start at zero: each call overwrites the
+ * part it reads. */
+size_t dsa_noalloc_max_mask_bytes(void);
+dsa_status dsa_attention_fwd_noalloc(const dsa_shape *shape, const void *Q, const void *K, const void *V,
+                                     const int8_t *Qt, const int8_t *Kt, float *O, void *stream);
+
 /* Step (a) alone with the smallest possible consumer, for measuring the int8 contraction:
  * rowmax[b,h,i] = max_j S~[b,h,i,j] (int32 [B,H,L]).  Uses B, H, L, k of the shape only. */
 dsa_status dsa_approx_rowmax(const dsa_shape *shape, const int8_t *Qt, const int8_t *Kt,

@@ -18,7 +18,8 @@ DSA_F32, DSA_BF16 = 0, 1
 
 EXPORTS = [
     "dsa_keep_from_ratio", "dsa_workspace_bytes", "dsa_predict_mask", "dsa_sddmm", "dsa_sparse_softmax",
-    "dsa_spmm", "dsa_masked_attention", "dsa_attention_fwd", "dsa_approx_rowmax", "dsa_mfma_i8_sustained",
+    "dsa_spmm", "dsa_masked_attention", "dsa_attention_fwd", "dsa_attention_fwd_noalloc",
+    "dsa_noalloc_max_mask_bytes", "dsa_approx_rowmax", "dsa_mfma_i8_sustained",
     "dsa_project_quantize", "dsa_project_workspace_bytes",
     "dsa_project_quantize_bits", "dsa_predict_workspace_bytes_bits", "dsa_predict_mask_bits",
     "dsa_workspace_bytes_bits", "dsa_attention_fwd_bits",
@@ -68,6 +69,10 @@ def lib():
         L.dsa_masked_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp]
         L.dsa_attention_fwd.restype = i32
         L.dsa_attention_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.dsa_attention_fwd_noalloc.restype = i32
+        L.dsa_attention_fwd_noalloc.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp]
+        L.dsa_noalloc_max_mask_bytes.restype = sz
+        L.dsa_noalloc_max_mask_bytes.argtypes = []
         L.dsa_approx_rowmax.restype = i32
         L.dsa_approx_rowmax.argtypes = [shp, vp, vp, vp, vp]
         L.dsa_project_workspace_bytes.restype = sz
@@ -226,6 +231,23 @@ def dsa_attention_fwd(shape, Q, K, V, Qt, Kt, O=None, idx_out=None, ws=None, wan
                                    _ptr(O), _ptr(idx_out), _ptr(ws), ws.numel(), _stream()),
            "dsa_attention_fwd")
     return O, idx_out
+
+
+def noalloc_max_mask_bytes() -> int:
+    return int(lib().dsa_noalloc_max_mask_bytes())
+
+
+def dsa_attention_fwd_noalloc(shape, Q, K, V, Qt, Kt, O):
+    """Whole path with the mask in the library's fixed device array; O must be given (the call
+    itself allocates nothing)."""
+    import torch
+    tq, tk, _, _ = _dims(shape)
+    dt = _qkv_dtype(shape)
+    _dev(Q, dt, tq); _dev(K, dt, tq); _dev(V, dt, tq); _dev(Qt, torch.int8, tk); _dev(Kt, torch.int8, tk)
+    _dev(O, torch.float32, tq)
+    _check(lib().dsa_attention_fwd_noalloc(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Qt), _ptr(Kt),
+                                           _ptr(O), _stream()), "dsa_attention_fwd_noalloc")
+    return O
 
 
 def dsa_approx_rowmax(shape, Qt, Kt, rowmax=None):

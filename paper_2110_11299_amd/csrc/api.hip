@@ -4,7 +4,34 @@
 
 #include <math.h>
 
+#include <atomic>
+
+// Mask storage for dsa_attention_fwd_noalloc: one array per GPU, held until the process ends.  In
+// host code this name is only a handle for hipGetSymbolAddress; kernels get the resolved address.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device, resolved once per device (two threads racing
+// on the first call both resolve the same address).
+hipError_t static_scratch(void **out)
+{
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev)) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return hipSuccess;
+}
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -134,6 +161,28 @@ dsa_status dsa_attention_fwd(const dsa_shape *sh, const void *Q, const void *K, 
     if (need && (!ws || ws_bytes < need)) return DSA_ERR_WORKSPACE;
     int32_t *idx = idx_out ? idx_out : static_cast<int32_t *>(ws);
     void *pws = idx_out ? ws : static_cast<void *>(static_cast<char *>(ws) + mask_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    if (hipError_t e = dsa::launch_predict(*sh, Qt, Kt, idx, pws, st)) return from_hip(e);
+    return from_hip(dsa::launch_attention(dsa::kFused, *sh, Q, K, V, idx, nullptr, nullptr, O, st));
+}
+
+size_t dsa_noalloc_max_mask_bytes(void) { return kStaticScratchBytes; }
+
+dsa_status dsa_attention_fwd_noalloc(const dsa_shape *sh, const void *Q, const void *K, const void *V,
+                                     const int8_t *Qt, const int8_t *Kt, float *O, void *stream)
+{
+    if (!sh || !Q || !K || !V || !Qt || !Kt || !O) return DSA_ERR_NULL;
+    if (dsa_status s = check_predict(sh)) return s;
+    if (dsa_status s = check_attention(sh)) return s;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(Qt) || !aligned16(Kt) || !aligned16(O))
+        return DSA_ERR_ALIGN;
+    const size_t mask_bytes = round_up_256(idx_bytes(*sh));
+    const size_t need = mask_bytes + round_up_256(dsa::predict_workspace_bytes(*sh));
+    if (need > kStaticScratchBytes) return DSA_ERR_WORKSPACE;
+    void *base = nullptr;
+    if (static_scratch(&base) != hipSuccess) return DSA_ERR_HIP;
+    int32_t *idx = static_cast<int32_t *>(base);
+    void *pws = static_cast<char *>(base) + mask_bytes;
     hipStream_t st = (hipStream_t)stream;
     if (hipError_t e = dsa::launch_predict(*sh, Qt, Kt, idx, pws, st)) return from_hip(e);
     return from_hip(dsa::launch_attention(dsa::kFused, *sh, Q, K, V, idx, nullptr, nullptr, O, st));

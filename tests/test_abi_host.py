@@ -118,3 +118,14 @@ def test_binding_refuses_cpu_tensors(b):
     t = torch.zeros((2, 2, 256, 32), dtype=torch.int8)
     with pytest.raises(ValueError):
         b.dsa_predict_mask(sh, t, t)
+
+
+def test_noalloc_rejects_masks_beyond_its_array_on_the_host(b):
+    """The size check of dsa_attention_fwd_noalloc comes before any device work."""
+    lib = b.lib()
+    assert b.noalloc_max_mask_bytes() == 16 << 20
+    big = b.make_shape(2, 8, 4096, 64, 32, 205, 1, b.DSA_BF16, 0.125)      # 53.7 MB of mask
+    fake = ctypes.c_void_p(0x1000)
+    st = lib.dsa_attention_fwd_noalloc(ctypes.byref(big), fake, fake, fake, fake, fake, fake, None)
+    assert st == 5 and "workspace" in b.status_string(st)
+    assert lib.dsa_attention_fwd_noalloc(ctypes.byref(big), None, fake, fake, fake, fake, fake, None) == 1
