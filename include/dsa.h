@@ -65,7 +65,8 @@ typedef enum { DSA_F32 = 0, DSA_BF16 = 1 } dsa_dtype;
  * section 4.2 for keep; section 5.1 for vec). */
 typedef struct {
     int32_t B, H;   /* batch, heads: B*H independent problems, each >= 1                      */
-    int32_t L;      /* sequence length, 1 <= L <= 32768 for the predictor, L % vec == 0       */
+    int32_t L;      /* sequence length, L % vec == 0; 1 <= L <= 32768 for the predictor,      */
+                    /* L <= 4194304 (2^22) for the attention entry points                     */
     int32_t d;      /* head dimension of Q, K, V: 64 or 128                                   */
     int32_t k;      /* projection dimension of Qt, Kt: a multiple of 16, 16 <= k <= 128       */
     int32_t keep;   /* kept keys per selection unit, 1 <= keep <= L (attention: <= 4096)      */

@@ -62,6 +62,7 @@ dsa_status check_attention(const dsa_shape *sh)
     if (sh->d != 64 && sh->d != 128) return DSA_ERR_UNSUPPORTED;
     if (sh->dtype != DSA_F32 && sh->dtype != DSA_BF16) return DSA_ERR_UNSUPPORTED;
     if (sh->keep > dsa::attention_max_keep()) return DSA_ERR_UNSUPPORTED;
+    if (sh->L > dsa::attention_max_L()) return DSA_ERR_UNSUPPORTED;
     if (!isfinite(sh->scale)) return DSA_ERR_SHAPE;
     return DSA_OK;
 }

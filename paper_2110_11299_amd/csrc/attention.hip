@@ -13,10 +13,7 @@
 namespace dsa {
 namespace {
 
-#ifndef DSA_ROW_WAVES
-#define DSA_ROW_WAVES 4
-#endif
-constexpr int kRowWaves = DSA_ROW_WAVES;   // query rows (wavefronts) per workgroup
+constexpr int kRowWaves = 4;          // query rows (wavefronts) per workgroup
 constexpr int kMaxKeep = 4096;        // list and scores of a row in LDS: 4 waves * 4096 * 8 B = 128 KB
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -149,10 +146,7 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
     float *sc = reinterpret_cast<float *>(sl + keep);
     for (int t = lane; t < keep; t += kWave) sl[t] = min(max(list[t], 0), L - 1);
     wave_lds_fence();
-#ifndef DSA_ATTN_U
-#define DSA_ATTN_U 4
-#endif
-    constexpr int U = DSA_ATTN_U;         // independent gathers in flight per lane
+    constexpr int U = 4;                  // independent gathers in flight per lane
 
     float m = -INFINITY;
     if (MODE != kSpmm) {
@@ -431,29 +425,17 @@ hipError_t launch_rows(AttnMode mode, const dsa_shape &sh, const void *Q, const 
     const T *q = static_cast<const T *>(Q), *k = static_cast<const T *>(K), *v = static_cast<const T *>(V);
     if (mode == kFused) {
         auto kern = attention_rows<T, D, kFused>;
-        if (lds > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
+        if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, st, q, k, v, idx, Pin, S, O, sh.L, sh.keep, sh.vec,
                            sh.scale, rows);
     } else if (mode == kSddmm) {
         auto kern = attention_rows<T, D, kSddmm>;
-        if (lds > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
+        if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, st, q, k, v, idx, Pin, S, O, sh.L, sh.keep, sh.vec, sh.scale,
                            rows);
     } else {
         auto kern = attention_rows<T, D, kSpmm>;
-        if (lds > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
+        if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, st, q, k, v, idx, Pin, S, O, sh.L, sh.keep, sh.vec, sh.scale,
                            rows);
     }
@@ -475,11 +457,7 @@ hipError_t launch_groups(const dsa_shape &sh, const void *Q, const void *K, cons
     const int keep_pad = (sh.keep + 31) / 32 * 32;
     const size_t lds = groups_lds_bytes(sh);
     auto kern = attention_groups_bf16<D>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
     hipLaunchKernelGGL(kern, dim3((groups + kGroupWaves - 1) / kGroupWaves), dim3(kGroupWaves * kWave), lds, st,
                        static_cast<const uint16_t *>(Q), static_cast<const uint16_t *>(K),
                        static_cast<const uint16_t *>(V), idx, O, sh.L, sh.keep, keep_pad, sh.scale, groups);
@@ -489,6 +467,9 @@ hipError_t launch_groups(const dsa_shape &sh, const void *Q, const void *K, cons
 }  // namespace
 
 int attention_max_keep() { return kMaxKeep; }
+
+// The row kernel forms element offsets inside one head (key index * d) in 32-bit arithmetic.
+int attention_max_L() { return 1 << 22; }
 
 hipError_t launch_attention(AttnMode mode, const dsa_shape &sh, const void *Q, const void *K,
                             const void *V, const int32_t *idx, const float *Pin, float *S, float *O,

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "dsa.h"
 
 namespace dsa {
@@ -22,9 +24,37 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned total)
     return x * q + (x < r ? x : r) + s;
 }
 
+// A kernel that wants more than the default 48 KB of dynamic LDS needs its limit raised first.  That
+// is done once per (kernel, device) and raises the limit to everything the device offers, so later
+// launches of the same kernel with any plan cost no runtime call.  (If the small table is full the
+// attribute is simply set again on every launch.)
+inline hipError_t allow_dynamic_lds(const void *kern, size_t bytes)
+{
+    if (bytes <= 48 * 1024) return hipSuccess;
+    struct Entry { const void *kern; int dev; };
+    static Entry done[128];
+    static int used = 0;
+    static std::mutex mu;
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev)) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < used; ++i)
+        if (done[i].kern == kern && done[i].dev == dev) return hipSuccess;
+    int limit = 0;
+    if (hipError_t e = hipDeviceGetAttribute(&limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev)) return e;
+    if ((size_t)limit < bytes) return hipErrorInvalidValue;
+    if (hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, limit)) return e;
+    if (used < 128) done[used++] = Entry{kern, dev};
+    return hipSuccess;
+}
+
 hipError_t launch_predict(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *idx,
                           void *ws, hipStream_t st);
 size_t predict_workspace_bytes(const dsa_shape &sh);
+// The streaming form of the fine-grained predictor and the shapes it serves (launch_predict picks it).
+bool stream_predict_fits(const dsa_shape &sh);
+hipError_t launch_predict_stream(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *idx,
+                                 hipStream_t st);
 
 enum AttnMode { kFused = 0, kSddmm = 1, kSpmm = 2 };
 hipError_t launch_attention(AttnMode mode, const dsa_shape &sh, const void *Q, const void *K,
@@ -43,6 +73,8 @@ hipError_t launch_mfma_i8_stream(int blocks, int iters, int32_t *sink, hipStream
 
 // Largest `keep` the attention kernels accept (scores of one row are staged in LDS).
 int attention_max_keep();
+// Largest L the attention kernels accept.
+int attention_max_L();
 // Largest L the predict kernel accepts.
 int predict_max_L();
 

@@ -3,54 +3,13 @@
 // (section 5.1), and the per-unit top-k that becomes the mask.  Scores are exact integers, so
 // the selection is exact: larger score first, lower key index among equals, list ascending.
 #include "dsa_internal.h"
-
-#include <stdlib.h>
+#include "wave_select.h"
 
 namespace dsa {
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-
 constexpr int kUnitThreads = 256;
 constexpr int kUnitMaxL = 32768;     // one unit's scores in LDS: 128 KB
-
-// Wavefront reductions without LDS traffic: butterfly inside each row of 16 lanes with DPP
-// (quad permutes, then the two mirrors), then the four row results through v_readlane into
-// scalar registers.  The result is wavefront-uniform and lives in an SGPR.
-template <int CTRL> __device__ __forceinline__ int dpp_move(int x)
-{
-    return __builtin_amdgcn_update_dpp(x, x, CTRL, 0xF, 0xF, false);
-}
-constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
-
-__device__ __forceinline__ int wave_sum(int x)
-{
-    x += dpp_move<kDppXor1>(x);
-    x += dpp_move<kDppXor2>(x);
-    x += dpp_move<kDppHalfMirror>(x);
-    x += dpp_move<kDppMirror>(x);
-    return __builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16) +
-           __builtin_amdgcn_readlane(x, 32) + __builtin_amdgcn_readlane(x, 48);
-}
-__device__ __forceinline__ int wave_max(int x)
-{
-    x = max(x, dpp_move<kDppXor1>(x));
-    x = max(x, dpp_move<kDppXor2>(x));
-    x = max(x, dpp_move<kDppHalfMirror>(x));
-    x = max(x, dpp_move<kDppMirror>(x));
-    return max(max(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
-               max(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
-}
-__device__ __forceinline__ int wave_min(int x)
-{
-    x = min(x, dpp_move<kDppXor1>(x));
-    x = min(x, dpp_move<kDppXor2>(x));
-    x = min(x, dpp_move<kDppHalfMirror>(x));
-    x = min(x, dpp_move<kDppMirror>(x));
-    return min(min(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
-               min(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
-}
 
 // One workgroup per selection unit.  All L scores of the unit are computed with packed int8
 // dot products into LDS; the keep-th largest value T is found by bisection on the value (the
@@ -175,38 +134,6 @@ __global__ __launch_bounds__(kUnitThreads) void predict_unit(const int8_t *__res
 // ---------------------------------------------------------------------------------------------
 constexpr int kTileUnits = 16;
 
-// Optional per-phase cycle accounting for tuning; compiled out of the library.
-#ifdef DSA_PHASE_TIMING
-__device__ unsigned long long g_phase_cycles[16];
-#define PHASE_MARK(slot)                                    \
-    do {                                                    \
-        const long long now_ = clock64();                   \
-        ph_[slot] += (unsigned long long)(now_ - t_phase_); \
-        t_phase_ = now_;                                    \
-    } while (0)
-#define PHASE_START()                                              \
-    unsigned long long ph_[16];                                    \
-    _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) ph_[i_] = 0; \
-    long long t_phase_ = clock64()
-#define PHASE_COUNT(slot, v) do { ph_[slot] += (unsigned long long)(v); } while (0)
-#define PHASE_FLUSH()                                                                                  \
-    do {                                                                                               \
-        if (lane == 0) {                                                                               \
-            _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) atomicAdd(&g_phase_cycles[i_], ph_[i_]); \
-        }                                                                                              \
-    } while (0)
-#else
-#define PHASE_MARK(slot) do { } while (0)
-#define PHASE_START() do { } while (0)
-#define PHASE_COUNT(slot, v) do { } while (0)
-#define PHASE_FLUSH() do { } while (0)
-#endif
-// Tuning aid: a build with -DDSA_PREDICT_STOP=n leaves the kernel after phase n (1 = A .. 3 = C); the
-// output is then meaningless.  Never defined for the library.
-#ifndef DSA_PREDICT_STOP
-#define DSA_PREDICT_STOP 0
-#endif
-
 constexpr int kCompactCap = 512;      // candidates of one unit that the register path handles
 constexpr int kSegSlots = 1024;       // segment slots per unit (all holders, all chunks)
 constexpr size_t kLdsBudget = 150 * 1024;       // of the 160 KB a gfx950 workgroup may use
@@ -233,145 +160,6 @@ template <> struct Mfma<64> {
         return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
     }
 };
-
-// Inclusive prefix sum over the 64 lanes: Hillis-Steele inside each row of 16 lanes with DPP row
-// shifts (zero fill), then the totals of the lower rows through v_readlane.  *total = wavefront sum.
-__device__ __forceinline__ int wave_incl_scan(int x, int lane, int *total)
-{
-    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, true);   // row_shr:1
-    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, true);   // row_shr:2
-    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, true);   // row_shr:4
-    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, true);   // row_shr:8
-    const int t0 = __builtin_amdgcn_readlane(x, 15), t1 = __builtin_amdgcn_readlane(x, 31),
-              t2 = __builtin_amdgcn_readlane(x, 47), t3 = __builtin_amdgcn_readlane(x, 63);
-    const int row = lane >> 4;
-    x += (row >= 1 ? t0 : 0) + (row >= 2 ? t1 : 0) + (row >= 3 ? t2 : 0);
-    *total = t0 + t1 + t2 + t3;
-    return x;
-}
-
-// Makes LDS writes of some lanes of a wavefront visible to reads of its other lanes.
-__device__ __forceinline__ void wave_lds_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// Exact score of (unit, key): sum over the unit's vec rows of the int8 dot product.
-__device__ __forceinline__ int unit_key_score(const int *__restrict__ qu, const int8_t *__restrict__ krow,
-                                              int vec, int k4)
-{
-    int s = 0;
-    for (int c4 = 0; c4 < k4; c4 += 4) {
-        const v4i kk = *reinterpret_cast<const v4i *>(krow + 4 * c4);
-        for (int r = 0; r < vec; ++r) {
-            const int *q = qu + r * k4 + c4;
-            s = __builtin_amdgcn_sdot4(q[0], kk.x, s, false);
-            s = __builtin_amdgcn_sdot4(q[1], kk.y, s, false);
-            s = __builtin_amdgcn_sdot4(q[2], kk.z, s, false);
-            s = __builtin_amdgcn_sdot4(q[3], kk.w, s, false);
-        }
-    }
-    return s;
-}
-
-// Number of (register, lane) pairs with v >= t for a wavefront-uniform t.  The compares are issued
-// back to back into separate mask registers and counted afterwards: with one shared mask register
-// every compare would wait for the scalar count of the one before it.
-__device__ __forceinline__ int count_ge4(int a, int b, int c, int d, int t)
-{
-    unsigned long long m0, m1, m2, m3;
-    asm("v_cmp_ge_i32_e64 %0, %4, %8\n\tv_cmp_ge_i32_e64 %1, %5, %8\n\t"
-        "v_cmp_ge_i32_e64 %2, %6, %8\n\tv_cmp_ge_i32_e64 %3, %7, %8"
-        : "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3)
-        : "v"(a), "v"(b), "v"(c), "v"(d), "s"(t));
-    return (__popcll(m0) + __popcll(m1)) + (__popcll(m2) + __popcll(m3));
-}
-__device__ __forceinline__ int count_ge8(int a, int b, int c, int d, int e, int f, int g, int h, int t)
-{
-    unsigned long long m0, m1, m2, m3, m4, m5, m6, m7;
-    asm("v_cmp_ge_i32_e64 %0, %8, %16\n\tv_cmp_ge_i32_e64 %1, %9, %16\n\t"
-        "v_cmp_ge_i32_e64 %2, %10, %16\n\tv_cmp_ge_i32_e64 %3, %11, %16\n\t"
-        "v_cmp_ge_i32_e64 %4, %12, %16\n\tv_cmp_ge_i32_e64 %5, %13, %16\n\t"
-        "v_cmp_ge_i32_e64 %6, %14, %16\n\tv_cmp_ge_i32_e64 %7, %15, %16"
-        : "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3), "=&s"(m4), "=&s"(m5), "=&s"(m6), "=&s"(m7)
-        : "v"(a), "v"(b), "v"(c), "v"(d), "v"(e), "v"(f), "v"(g), "v"(h), "s"(t));
-    return ((__popcll(m0) + __popcll(m1)) + (__popcll(m2) + __popcll(m3))) +
-           ((__popcll(m4) + __popcll(m5)) + (__popcll(m6) + __popcll(m7)));
-}
-__device__ __forceinline__ int count_ge2(int a, int b, int t)
-{
-    unsigned long long m0, m1;
-    asm("v_cmp_ge_i32_e64 %0, %2, %4\n\tv_cmp_ge_i32_e64 %1, %3, %4"
-        : "=&s"(m0), "=&s"(m1)
-        : "v"(a), "v"(b), "s"(t));
-    return __popcll(m0) + __popcll(m1);
-}
-template <int NR, int USED>
-__device__ __forceinline__ int count_ge(const int (&v)[NR], int t)
-{
-    int cnt = 0;
-    int i = 0;
-#pragma unroll
-    for (; i + 8 <= USED; i += 8)
-        cnt += count_ge8(v[i], v[i + 1], v[i + 2], v[i + 3], v[i + 4], v[i + 5], v[i + 6], v[i + 7], t);
-    if (USED - i >= 4) { cnt += count_ge4(v[i], v[i + 1], v[i + 2], v[i + 3], t); i += 4; }
-    if (USED - i >= 2) { cnt += count_ge2(v[i], v[i + 1], t); i += 2; }
-    if (USED - i >= 1) cnt += __popcll(__ballot(v[i] >= t));
-    return cnt;
-}
-
-// The keep-th largest of the values a wavefront holds in registers (NR per lane, unused slots
-// INT32_MIN): the largest T with count(v >= T) >= keep, by bisection on the value.  lo and hi are
-// wavefront-uniform; needs count(v >= lo) >= keep and hi >= every value.  Every probe is above
-// INT32_MIN, so unused slots never count.  With slack > 0 the search stops at the first T whose
-// count lies in [keep, keep + slack]: still a lower bound of the keep-th largest, found sooner.
-template <int NR, int USED = NR>
-__device__ __forceinline__ int kth_largest(const int (&v)[NR], int keep, int lo, int hi, int slack = 0)
-{
-    lo = __builtin_amdgcn_readfirstlane(lo);
-    hi = __builtin_amdgcn_readfirstlane(hi);
-    // One exit test per round keeps the loop a handful of scalar instructions around the compares;
-    // the scalar unit is shared by all wavefronts of the compute unit and they all sit in this loop
-    // at the same time.  |values| < 2^30, so lo + hi cannot overflow.
-    bool more = lo < hi;
-    while (more) {
-        const int mid = (lo + hi + 1) >> 1;
-        const int cnt = count_ge<NR, USED>(v, mid);
-        const bool ge = cnt >= keep;
-        lo = ge ? mid : lo;
-        hi = ge ? hi : mid - 1;
-        // slack > 0: any T with keep <= count(v >= T) <= keep + slack will do
-        more = lo < hi && (unsigned)(cnt - keep) > (unsigned)slack;
-    }
-    return lo;
-}
-
-// kth_largest over the first `used` (wavefront-uniform) registers only.
-template <int NR>
-__device__ __forceinline__ int kth_largest_of(const int (&v)[NR], int used, int keep, int lo, int hi, int slack = 0)
-{
-    switch (used) {
-    case 1: return kth_largest<NR, 1>(v, keep, lo, hi, slack);
-    case 2: return kth_largest<NR, (NR >= 2 ? 2 : NR)>(v, keep, lo, hi, slack);
-    case 3: return kth_largest<NR, (NR >= 3 ? 3 : NR)>(v, keep, lo, hi, slack);
-    case 4: return kth_largest<NR, (NR >= 4 ? 4 : NR)>(v, keep, lo, hi, slack);
-    case 5: return kth_largest<NR, (NR >= 5 ? 5 : NR)>(v, keep, lo, hi, slack);
-    case 6: return kth_largest<NR, (NR >= 6 ? 6 : NR)>(v, keep, lo, hi, slack);
-    default: return kth_largest<NR>(v, keep, lo, hi, slack);
-    }
-}
-
-// m with all but its r lowest set bits cleared (r <= 0: none kept).
-__device__ __forceinline__ unsigned lowest_set_bits(unsigned m, int r)
-{
-    if (r <= 0) return 0u;
-    if (r >= __popc(m)) return m;
-    unsigned rest = m;
-    for (int i = 0; i < r; ++i) rest &= rest - 1;
-    return m & ~rest;
-}
 
 // (A) for one wavefront and one chunk: scores of TC tiles into registers plus bucket maxima.
 // Key rows are loaded unconditionally from clamped addresses: a key beyond L only feeds output
@@ -505,7 +293,6 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
     }
     __syncthreads();
 
-    PHASE_START();
     for (int chunk = 0; chunk < nchunks; ++chunk) {
         const int chunk_base = chunk * chunk_keys;
         const int wave_lo = chunk_base + w * kTileUnits * TC;          // first key of this wavefront
@@ -532,10 +319,7 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
         // (B) lower bound T0 per unit from the bucket maxima
 #pragma unroll
         for (int b = 0; b < NB; ++b) bm[c * NBTp + (4 * w + g) * NB + b] = bmax[b];
-        PHASE_MARK(0);
-        if (DSA_PREDICT_STOP == 1) continue;
         __syncthreads();
-        PHASE_MARK(1);
         // Buckets follow key order inside the chunk, so the ones that hold a real key are the first
         // `real` of them; the others keep INT32_MIN.
         const int bucket_keys = 4 * TC / NB;
@@ -571,10 +355,7 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
             }
             if (lane == 0) T0s[uu] = max(T0s[uu], T);
         }
-        PHASE_MARK(2);
-        if (DSA_PREDICT_STOP == 2) continue;
         __syncthreads();
-        PHASE_MARK(3);
 
         // (C) candidates: bit j of a unit's bitmap = score(unit, key j) >= thr; passing scores are
         // appended, in key order, to this holder's segment.  thr is T0.
@@ -622,7 +403,6 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
                     if (pos0 >= HC) wrapf[c] = 1;
                 }
             }
-            PHASE_MARK(4);
             if (nchunks != 1) break;
             __syncthreads();              // also the barrier in front of (D)
             if (pass) break;
@@ -635,9 +415,7 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
         }
         // bm / T0s are rewritten only after the next chunk's first barrier
     }
-    if (DSA_PREDICT_STOP >= 1 && DSA_PREDICT_STOP <= 3) { __syncthreads(); continue; }
     if (nchunks != 1) __syncthreads();
-    PHASE_MARK(5);
 
     // (D) exact selection among the candidates, one wavefront per unit
     const int k4 = k / 4;
@@ -657,8 +435,6 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
         for (int h = lane; h < NHT; h += kWave) nc += cu[h];
         nc = wave_sum(nc);
         const bool fits = nc <= kCompactCap;
-        PHASE_COUNT(12, nc);
-        PHASE_COUNT(13, 1);
 
         if (strict[uu] && nc < keep) {
             // fewer than keep scores above T0 and at least keep at or above it: the keep-th largest is
@@ -760,8 +536,6 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
                 }
             }
             wave_lds_sync();
-            PHASE_MARK(6);
-            if (DSA_PREDICT_STOP == 4) { if (lane == 0) out[0] = compact[nc - 1].x; continue; }
             constexpr int NR = kCompactCap / kWave;
             const int groups = (nc + kWave - 1) / kWave;
             int sc[NR], ck[NR];
@@ -777,11 +551,8 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
                 if (b * kWave + lane >= nc) sc[b] = INT32_MIN;
                 hi = max(hi, sc[b]);
             }
-            PHASE_MARK(7);
             // every candidate reaches T0 and there are at least keep of them
             const int T = kth_largest_of<NR>(sc, groups, keep, lo0, wave_max(hi));
-            PHASE_MARK(8);
-            if (DSA_PREDICT_STOP == 5) { if (lane == 0) out[0] = T; continue; }
             int gt = 0;
 #pragma unroll
             for (int b = 0; b < NR; ++b)
@@ -801,9 +572,7 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
                 }
             }
             wave_lds_sync();      // the next unit reuses `compact`
-            PHASE_MARK(9);
         } else {
-            PHASE_COUNT(15, 1);
             // Too many candidates (massive ties or a very large keep): the same steps over all keys,
             // recomputing the score of every flagged key in every pass.
             auto flagged_score = [&](int j) -> int {
@@ -840,7 +609,6 @@ __global__ __launch_bounds__(MAXW *kWave) void predict_tiles(const int8_t *__res
     }
     __syncthreads();      // the next tile reuses every LDS array
     }
-    PHASE_FLUSH();
 }
 
 struct TilePlan {
@@ -924,11 +692,7 @@ hipError_t launch_tiles_t(const TilePlan &p, const dsa_shape &sh, const int8_t *
                           int32_t *idx, hipStream_t st)
 {
     auto kern = predict_tiles<TC, NB, KSTEP, MAXSTEPS, MAXW>;
-    if (p.lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds);
-        if (e != hipSuccess) return e;
-    }
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), p.lds)) return e;
     const unsigned tiles = (unsigned)sh.B * sh.H * p.tiles_per_head;
     // one workgroup per compute unit (a multiple of the XCD count), each looping over tiles
     unsigned resident = 0;
@@ -1038,11 +802,8 @@ __global__ __launch_bounds__(512) void rowmax_mfma(
             for (int s = 0; s < KSTEPS; ++s)
                 cur[h] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[s], qop[h][s], cur[h], 0, 0, 0);
         }
-#ifndef DSA_ROWMAX_EXPERIMENT
-#define DSA_ROWMAX_EXPERIMENT 0     // tuning aid, never set for the library
-#endif
 #pragma unroll
-        for (int r = 0; r < (DSA_ROWMAX_EXPERIMENT == 1 ? 2 : DSA_ROWMAX_EXPERIMENT == 2 ? 8 : 16); r += 2) {
+        for (int r = 0; r < 16; r += 2) {
 #pragma unroll
             for (int h = 0; h < NQ; ++h) m[h] = max(max(prev[h][r], prev[h][r + 1]), m[h]);
         }
@@ -1092,17 +853,6 @@ __global__ __launch_bounds__(512) void rowmax_mfma(
 
 }  // namespace
 
-#ifdef DSA_PHASE_TIMING
-extern "C" void dsa_debug_phase_cycles(unsigned long long *host16, int reset)
-{
-    if (host16) (void)hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_phase_cycles), sizeof(g_phase_cycles));
-    if (reset) {
-        unsigned long long z[16] = {0};
-        (void)hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), z, sizeof(z));
-    }
-}
-#endif
-
 int predict_max_L() { return kUnitMaxL; }
 
 size_t predict_workspace_bytes(const dsa_shape &) { return 0; }
@@ -1110,29 +860,18 @@ size_t predict_workspace_bytes(const dsa_shape &) { return 0; }
 hipError_t launch_predict(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *idx, void *,
                           hipStream_t st)
 {
-    static const bool use_unit_kernel = [] {
-        const char *e = getenv("DSA_PREDICT_IMPL");
-        return e && e[0] == 'u';
-    }();
+    if (stream_predict_fits(sh)) return launch_predict_stream(sh, Qt, Kt, idx, st);
     const TilePlan plan = plan_tiles(sh);
-    if (!use_unit_kernel && plan.ok) return launch_tiles(plan, sh, Qt, Kt, idx, st);
+    if (plan.ok) return launch_tiles(plan, sh, Qt, Kt, idx, st);
     const unsigned units = (unsigned)sh.B * sh.H * (sh.L / sh.vec);
     const size_t lds = ((size_t)sh.L + sh.vec * (sh.k / 4) + 8) * sizeof(int);
     if (sh.vec == 1) {
         auto kern = predict_unit<1>;
-        if (lds > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
+        if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
         hipLaunchKernelGGL(kern, dim3(units), dim3(kUnitThreads), lds, st, Qt, Kt, idx, sh.L, sh.k, sh.keep);
     } else {
         auto kern = predict_unit<8>;
-        if (lds > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
+        if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
         hipLaunchKernelGGL(kern, dim3(units), dim3(kUnitThreads), lds, st, Qt, Kt, idx, sh.L, sh.k, sh.keep);
     }
     return hipGetLastError();

@@ -1,0 +1,581 @@
+// Fine-grained predictor in streaming form (paper section 3.1: approximate scores S~ = Q~ K~^T
+// and the per-row top-k that becomes the mask; section 3.4: the score contraction is cheap, "a
+// low-precision GEMM").  For vec = 1 the contraction is so cheap on the int8 matrix cores (7 us
+// for all of L = 4096, 16 heads) that it pays to compute it twice and never keep a score:
+//
+//   One wavefront owns 16 selection units (query rows) of one head and streams all L keys, with
+//   no other wavefront to wait for: no workgroup barrier anywhere.  Matrix-core orientation: keys
+//   are the rows (A operand), the 16 units the columns (B operand) of
+//   v_mfma_i32_16x16x{32,64}_i8.  Lane (c = lane % 16, g = lane / 16) receives, per tile, the
+//   scores of unit c against 4 consecutive keys of quarter g of the key range.  Every phase keeps
+//   that layout: the four lanes (c, 0..3) work for unit c, so all 16 units advance together in
+//   plain vector instructions, with no scalar bookkeeping and no serial chain per unit.
+//
+//   pass 1  stream the keys; every lane keeps NB maxima over disjoint key sets ("buckets", tile
+//           t of a quarter belongs to bucket t % NB): half a vector operation per score.
+//   bound   T0 = the keep-th largest of a unit's 4*NB bucket maxima (a few more are accepted): at
+//           least keep keys reach T0, so T0 is a lower bound of the keep-th largest score.  Every
+//           unit bisects on the value, each lane counting its own maxima.
+//   pass 2  stream the keys again; compare every score with T0 and shift the outcome into a
+//           32-bit word (compare into carry, add with carry): the words are the unit's bitmap of
+//           candidate keys, in key order.
+//   list    every lane turns its words into key indices, appended to its unit's list in LDS at the
+//           offset its quarter starts at: the list is in key order.
+//   scores  the list is dealt out again in four equal runs, one per lane of the unit (whatever the
+//           distribution of the candidates over the key range); each lane recomputes the scores of
+//           its run with packed dot products (about 1.25 * keep per unit) into registers.
+//   select  exact threshold T = keep-th largest candidate score by bisection on the value, again all
+//           units at once; then keys with score > T, and the first keys with score == T in key
+//           order, are placed through running counts into an LDS image of the 16 index rows,
+//           which leaves as one contiguous block.
+#include "dsa_internal.h"
+#include "wave_select.h"
+
+#include <algorithm>
+
+namespace dsa {
+namespace {
+
+constexpr int kStreamUnits = 16;        // units per wavefront: the columns of one matrix instruction
+constexpr int kStreamSlots = 88;        // candidate scores a lane holds in registers
+constexpr int kStreamCap = 4 * kStreamSlots;   // candidates of one unit (its four lanes)
+constexpr int kStreamStride = kStreamCap + 2;  // list entries per unit in LDS: one spare slot, kept even
+constexpr int kStreamMaxL = 8192;       // bitmap of 16 units in LDS: 2 * L bytes per wavefront
+constexpr int kStreamPrefetch = 8;      // key tiles requested ahead of their use
+constexpr int kStreamWaves = 8;         // wavefronts (tasks) per workgroup: two per SIMD
+constexpr int kStreamLongNB = 128;      // bucket maxima per lane for long sequences
+
+// The key stream of one wavefront: scores of tile t (16 keys x 16 units) from v_mfma_i32_16x16x64_i8.
+// A matrix row is 64 bytes of contraction, i.e. R = 64 / K keys side by side: every lane loads 16
+// bytes (a quarter, half or all of one key row, the widest load there is, which is what the vector
+// memory path delivers best), and tile i of the R tiles that share a row operand is obtained with a
+// unit operand that holds Q~ in the lanes of key i and zero in the others.  Row r of tile t is key
+// (r / 4) * Lq + 4 t + r % 4, so lane (c, g) receives keys g * Lq + 4 t + {0..3} of unit c.
+// Row operands sit in a ring and are requested 8 tiles before their use; the matrix core runs two
+// tiles ahead of the consumer.  That distance is not only for speed: the consumers of a score include
+// hand-written instruction pairs, for which the compiler inserts no wait for a matrix result, so a
+// whole tile of vector work always lies between a matrix instruction and the first read of its result
+// (in-order issue, pinned by the scheduling barriers of the callers).
+template <int K> struct KeyStream {
+    static constexpr int R = 64 / K;            // keys per matrix row = tiles per ring slot
+    static constexpr int LPK = K / 16;          // lanes (16-byte parts) per key row
+    static constexpr int NS = 8 / R;            // ring slots: 8 tiles in flight
+    static constexpr unsigned kSlotStep = 256;  // bytes between the rows of consecutive slots: 4 * R * K
+    const int8_t *Kh;
+    unsigned off0, off_last;
+    v4i qv[R], ring[NS], p0, p1;
+
+    static __device__ __forceinline__ v4i load16(const int8_t *p) { return *reinterpret_cast<const v4i *>(p); }
+
+    template <bool SAFE> __device__ __forceinline__ void issue(int t8, int jn, unsigned next)
+    {
+        const int slot = (jn % 8) / R;
+        p1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(ring[slot], qv[jn % R], v4i{0, 0, 0, 0}, 0, 0, 0);
+        if (jn % R == R - 1) {                  // the slot's last tile is on its way: request what comes 8 tiles later
+            unsigned off = next + (unsigned)(jn / R) * kSlotStep;
+            if (SAFE) off = min(off, off_last);
+            ring[slot] = load16(Kh + off);
+        }
+    }
+    // Byte offset of the row operand that holds tile t8 + 8 (t8 a multiple of 8).
+    __device__ __forceinline__ unsigned next_of(int t8) const { return off0 + (unsigned)(t8 / R + NS) * kSlotStep; }
+
+    // Starts the stream: operands of tiles 0..7, tiles 0 and 1 issued.  Rows beyond L read row L - 1.
+    __device__ __forceinline__ void start(const int8_t *Kh_, const int8_t *Qrow, bool unit_live, int lane, int Lq, int L)
+    {
+        Kh = Kh_;
+        const int r = lane & 15, kb = lane >> 4, sub = kb / LPK, part = kb % LPK;
+        off0 = (unsigned)((r >> 2) * Lq + 4 * sub + (r & 3)) * (unsigned)K + 16u * part;
+        off_last = (unsigned)(L - 1) * (unsigned)K + 16u * part;
+#pragma unroll
+        for (int i = 0; i < R; ++i)
+            qv[i] = (unit_live && sub == i) ? load16(Qrow + 16 * part) : v4i{0, 0, 0, 0};
+        restart();
+    }
+    __device__ __forceinline__ void restart()
+    {
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) ring[sl] = load16(Kh + min(off0 + (unsigned)sl * kSlotStep, off_last));
+        const unsigned next = next_of(0);
+        issue<true>(0, 0, next);
+        p0 = p1;
+        issue<true>(0, 1, next);
+    }
+    // Scores of tile t8 + j (j = 0..7, a constant after unrolling); issues tile t8 + j + 2.
+    template <bool SAFE> __device__ __forceinline__ v4i next_tile(int t8, int j, unsigned next)
+    {
+        const v4i cur = p0;
+        p0 = p1;
+        issue<SAFE>(t8, j + 2, next);          // tile t8 + j + 2 (for j > 5 a tile of the next group)
+        return cur;
+    }
+};
+
+// cnt += (v >= t), per lane: compare into the carry, add with carry.
+__device__ __forceinline__ void count_if_ge(int &cnt, int v, int t)
+{
+    asm("v_cmp_ge_i32 vcc, %1, %2\n\tv_addc_co_u32 %0, vcc, 0, %0, vcc" : "+v"(cnt) : "v"(v), "v"(t) : "vcc");
+}
+// word = 2 * word + (v >= t), per lane.
+__device__ __forceinline__ void shift_in_ge(unsigned &word, int v, int t)
+{
+    asm("v_cmp_ge_i32 vcc, %1, %2\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(word) : "v"(v), "v"(t) : "vcc");
+}
+
+// v = (key < L) ? v : INT32_MIN, per lane, as one inseparable pair (a plain compare per score of an
+// unrolled round would be hoisted by the hundreds and exhaust the scalar registers).
+__device__ __forceinline__ int mask_beyond(int v, int key, int L)
+{
+    asm("v_cmp_lt_i32 vcc, %1, %2\n\tv_cndmask_b32 %0, %3, %0, vcc" : "+v"(v) : "v"(key), "v"(L), "v"(INT32_MIN) : "vcc");
+    return v;
+}
+
+// Sum / minimum / maximum over the four lanes (c, 0..3) that share a unit; every one of them gets it.
+__device__ __forceinline__ int unit_sum(int x)
+{
+    x += __shfl_xor(x, 16, kWave);
+    return x + __shfl_xor(x, 32, kWave);
+}
+__device__ __forceinline__ int unit_min(int x)
+{
+    x = min(x, __shfl_xor(x, 16, kWave));
+    return min(x, __shfl_xor(x, 32, kWave));
+}
+__device__ __forceinline__ int unit_max(int x)
+{
+    x = max(x, __shfl_xor(x, 16, kWave));
+    return max(x, __shfl_xor(x, 32, kWave));
+}
+
+// Geometry shared by the kernel and the host: the key range is cut into four quarters of Lq keys
+// (a multiple of 32, so that a quarter is a whole number of bitmap words), quarter g = lane / 16.
+__host__ __device__ inline int stream_quarter(int L) { return (L + 127) / 128 * 32; }
+
+// One group of 8 tiles of pass 1 (t8, the group's first tile, is a multiple of 8).  SAFE: the group may
+// touch keys beyond L or tiles beyond the quarter: requests are clamped to the last key row and such
+// scores become INT32_MIN.
+template <bool SAFE, int K, int NB>
+__device__ __forceinline__ void pass1_group(int (&bmax)[NB], KeyStream<K> &ks, int t8, int b0, int key_lo, int key_lim)
+{
+    const unsigned next = ks.next_of(t8);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        v4i cur = ks.template next_tile<SAFE>(t8, j, next);
+        if (SAFE) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) cur[i] = mask_beyond(cur[i], key_lo + 4 * (t8 + j) + i, key_lim);
+        }
+        bmax[b0 + j] = max(max(bmax[b0 + j], cur[0]), max(max(cur[1], cur[2]), cur[3]));
+        __builtin_amdgcn_sched_barrier(0);                           // keep the stream in order
+    }
+}
+
+// One bitmap word of pass 2: 8 tiles, 32 consecutive keys of this lane's quarter.
+template <bool SAFE, int K>
+__device__ __forceinline__ unsigned pass2_word(KeyStream<K> &ks, int t8, int T0)
+{
+    const unsigned next = ks.next_of(t8);
+    unsigned word = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const v4i cur = ks.template next_tile<SAFE>(t8, j, next);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) shift_in_ge(word, cur[i], T0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    return __brev(word);          // the first key of the word was shifted in first
+}
+
+// Exclusive prefix and total of a per-lane count over the four lanes (c, 0..3) of a unit, in lane
+// order g = 0..3.
+__device__ __forceinline__ int unit_excl_scan(int x, int g, int *total)
+{
+    const int s1 = __shfl_xor(x, 16, kWave);      // lane g ^ 1
+    const int s2 = __shfl_xor(x, 32, kWave);      // lane g ^ 2
+    const int s3 = __shfl_xor(s1, 32, kWave);     // lane g ^ 3
+    *total = x + s1 + s2 + s3;
+    // g ^ 1 < g iff bit 0 of g is set; g ^ 2 < g and g ^ 3 < g iff bit 1 is set
+    return ((g & 1) ? s1 : 0) + ((g & 2) ? s2 + s3 : 0);
+}
+
+// K is the projection dimension k (a template argument, so that the byte offsets of the key stream
+// are constants).
+template <int K, int NB>
+__global__ __launch_bounds__(kStreamWaves *kWave) void predict_stream(const int8_t *__restrict__ Qt,
+                                                           const int8_t *__restrict__ Kt,
+                                                           int32_t *__restrict__ idx, int L, int keep,
+                                                           int tasks_per_head, unsigned total_tasks,
+                                                           int lds_words_per_wave)
+{
+    constexpr int k = K;
+    constexpr int PF = kStreamPrefetch;
+    static_assert(PF == 8 && NB % 8 == 0, "groups of 8 tiles: one trip of the ring, one bitmap word");
+    extern __shared__ unsigned smem_all[];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int c = lane & 15, g = lane >> 4;
+    unsigned *smem = smem_all + wave * lds_words_per_wave;
+    // The wavefronts of a workgroup are independent (each has its own task and its own LDS) but start
+    // together on consecutive tasks of one head: they sweep the same keys at the same pace, so one
+    // compute unit's L1 serves most of their key requests.  A wavefront without a task mirrors the
+    // last one and writes nothing.
+    const unsigned slot = xcd_contiguous(blockIdx.x, gridDim.x) * kStreamWaves + wave;
+    const bool task_live = slot < total_tasks;
+    const unsigned task = task_live ? slot : total_tasks - 1;
+    const unsigned n = task / (unsigned)tasks_per_head;
+    const int u0 = (int)(task % (unsigned)tasks_per_head) * kStreamUnits;
+    const int nu = min(kStreamUnits, L - u0);    // real units of this wavefront
+    const int Lq = stream_quarter(L);
+    const int NT = Lq / 4;                       // tiles of 4 keys per quarter: a multiple of 8
+    const int NWL = Lq / 32;                     // bitmap words per lane
+    // LDS: [bitmap: word w of lane l at w * 64 + l | later the image of the 16 index rows][lists]
+    unsigned *bitmap = smem;
+    const int head_words = max(NWL * kWave, (kStreamUnits * keep + 2) / 2);       // rows: one spare slot
+    uint16_t *rows = reinterpret_cast<uint16_t *>(smem);                       // [16][keep]
+    uint16_t *list = reinterpret_cast<uint16_t *>(smem + head_words) + c * kStreamStride;   // this unit's list
+
+    const int8_t *Kh = Kt + (size_t)n * L * k;
+    const int8_t *Qh = Qt + (size_t)n * L * k;
+    const bool unit_live = u0 + c < L;
+
+    // tiles [0, tfull) hold only real keys in all four quarters
+    int tfull = NT;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) tfull = min(tfull, max(0, min(L - q * Lq, Lq)) / 4);
+    const int key_lo = g * Lq;                   // first key of this lane's quarter
+    const int key_lim = min(L, key_lo + Lq);     // its keys are below key_lim
+
+    KeyStream<K> ks;
+    ks.start(Kh, Qh + (size_t)min(u0 + c, L - 1) * k, unit_live, lane, Lq, L);
+
+    // ---- pass 1: bucket maxima -----------------------------------------------------------------
+    int bmax[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) bmax[b] = INT32_MIN;
+    {
+        for (int t0 = 0; t0 < NT; t0 += NB) {
+#pragma unroll
+            for (int b0 = 0; b0 < NB; b0 += 8) {
+                const int t8 = t0 + b0;
+                if (t8 < NT) {
+                    // a group is plain when it and every request it makes stay inside the full tiles
+                    if (t8 + 8 + 2 + PF <= tfull)
+                        pass1_group<false, K, NB>(bmax, ks, t8, b0, key_lo, key_lim);
+                    else
+                        pass1_group<true, K, NB>(bmax, ks, t8, b0, key_lo, key_lim);
+                }
+            }
+        }
+    }
+
+    // ---- bound: T0 per unit, 16 units at once ---------------------------------------------------
+    int T0;
+    {
+        int lo = INT32_MAX, hi = INT32_MIN;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            lo = min(lo, bmax[b]);
+            hi = max(hi, bmax[b]);
+        }
+        // an empty bucket holds INT32_MIN: start below every possible score instead (the host only
+        // takes this kernel when at least keep buckets of a unit hold a key)
+        lo = max(unit_min(lo), -(k * 127 * 127) - 1);
+        hi = max(unit_max(hi), lo);
+        // Invariant: count(maxima >= lo) >= keep, count(maxima >= hi + 1) < keep.  A unit is done when
+        // lo == hi, or as soon as a probe lands within `slack` of keep.
+        const int slack = keep >> 4;
+        while (__ballot(lo < hi) != 0) {
+            const int mid = (lo + hi + 1) >> 1;     // == lo for a finished unit
+            int cnt = 0;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) count_if_ge(cnt, bmax[b], mid);
+            cnt = unit_sum(cnt);
+            const bool ge = cnt >= keep;
+            lo = ge ? mid : lo;
+            hi = ge ? hi : mid - 1;
+            if (ge && cnt - keep <= slack) hi = lo;
+        }
+        T0 = lo;
+    }
+
+    // ---- pass 2: bitmap of candidates (score >= T0) ----------------------------------------------
+    __syncthreads();                             // start the second sweep together as well
+    int mine = 0;                                // candidates in this lane's quarter
+    {
+        ks.restart();
+        for (int w = 0; w < NWL; ++w) {
+            unsigned word;
+            if (8 * w + 8 + 2 + PF <= tfull) {
+                word = pass2_word<false, K>(ks, 8 * w, T0);
+            } else {
+                word = pass2_word<true, K>(ks, 8 * w, T0);
+                const int nv = key_lim - (key_lo + 32 * w);      // real keys in this word
+                word = nv >= 32 ? word : nv <= 0 ? 0u : word & ((1u << nv) - 1u);
+            }
+            bitmap[w * kWave + lane] = word;
+            mine += __popc(word);
+        }
+    }
+
+    // ---- list: candidate keys of every unit in key order ----------------------------------------
+    int nc;
+    {
+        int pos = unit_excl_scan(mine, g, &nc);
+        for (int w = 0; w < NWL; ++w) {
+            unsigned m = bitmap[w * kWave + lane];          // this lane's own word: no fence needed
+            // the wait for this read belongs here, once per word: left to the first use of m it would sit in
+            // the loop below and also wait, on every trip, for the list write of the trip before
+            asm volatile("" : "+v"(m));
+            const int key1 = key_lo + 32 * w - 1;
+            // one bit per trip and lane, no branch inside: a lane with nothing left (or no room) writes
+            // to the spare slot behind its unit's list
+            while (__ballot(m != 0u) != 0) {
+                const bool put = m != 0u && pos < kStreamCap;
+                list[put ? pos : kStreamCap] = (uint16_t)(key1 + __ffs(m));
+                pos += m != 0u;
+                m &= m - 1u;
+            }
+        }
+    }
+    wave_lds_sync();
+    const bool fits = nc <= kStreamCap;
+    const unsigned long long below = (1ull << lane) - 1ull;
+
+    // Units whose candidates do not fit (a plateau of equal scores at T0, or a bound that is not tight):
+    // the whole wavefront works on one such unit, recomputing the score of every flagged key in
+    // every pass, and writes its row straight to memory.
+    for (unsigned long long todo = __ballot(!fits && unit_live && g == 0); todo != 0; todo &= todo - 1) {
+        const int uu = __ffsll((long long)todo) - 1;             // lane index = unit index for g == 0
+        const int lo0 = __builtin_amdgcn_readlane(T0, uu);
+        const int *qu = reinterpret_cast<const int *>(Qh + (size_t)(u0 + uu) * k);
+        int32_t *out = idx + ((size_t)n * L + u0 + uu) * keep;
+        auto flagged_score = [&](int j) -> int {
+            if (j >= L) return INT32_MIN;
+            const int q = j / Lq, r = j - q * Lq;               // quarter, key inside it
+            if (!((bitmap[(r >> 5) * kWave + 16 * q + uu] >> (r & 31)) & 1u)) return INT32_MIN;
+            return unit_key_score(qu, Kh + (size_t)j * k, 1, k / 4);
+        };
+        int hi = INT32_MIN;
+        for (int j = lane; j < L; j += kWave) hi = max(hi, flagged_score(j));
+        hi = wave_max(hi);
+        int lo = lo0;
+        while (lo < hi) {
+            const int mid = (int)(lo + ((long long)hi - lo + 1) / 2);
+            int ge = 0;
+            for (int j0 = 0; j0 < L; j0 += kWave) ge += __popcll(__ballot(flagged_score(j0 + lane) >= mid));
+            if (ge >= keep) lo = mid; else hi = mid - 1;
+        }
+        const int T = lo;
+        int gt = 0;
+        for (int j0 = 0; j0 < L; j0 += kWave) gt += __popcll(__ballot(flagged_score(j0 + lane) > T));
+        const int need_eq = keep - gt;
+        int out_base = 0, eq_base = 0;
+        for (int j0 = 0; j0 < L; j0 += kWave) {
+            const int j = j0 + lane;
+            const int s = flagged_score(j);
+            const bool eq = s == T;          // T >= T0 > INT32_MIN, so unflagged keys never match
+            const unsigned long long meq = __ballot(eq);
+            const bool sel = s > T || (eq && eq_base + __popcll(meq & below) < need_eq);
+            const unsigned long long msel = __ballot(sel);
+            if (sel && task_live) out[out_base + __popcll(msel & below)] = j;
+            out_base += __popcll(msel);
+            eq_base += __popcll(meq);
+        }
+    }
+
+    // ---- scores: lane (c, g) takes run g of its unit's list --------------------------------------
+    const bool active = fits && unit_live;
+    const int run = active ? (nc + 3) >> 2 : 0;          // candidates per lane, <= kStreamSlots
+    const int first = g * run;
+    const int run_max = wave_max(run);                   // wavefront-uniform
+    int qrow[K / 4];
+#pragma unroll
+    for (int i = 0; i < K / 4; ++i)
+        qrow[i] = reinterpret_cast<const int *>(Qh + (size_t)min(u0 + c, L - 1) * k)[i];
+    int sc[kStreamSlots];
+    int top = INT32_MIN;
+#pragma unroll
+    for (int j0 = 0; j0 < kStreamSlots; j0 += 8) {
+        if (j0 < run_max) {
+            // eight candidates at a time: their keys, then all their key rows in flight, then the dots
+            int key[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                key[j] = min((int)list[min(first + j0 + j, kStreamCap - 1)], L - 1);      // never outside K~
+            v4i kk[8][K / 16];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const v4i *kr = reinterpret_cast<const v4i *>(Kh + (size_t)((unsigned)key[j] * (unsigned)k));
+#pragma unroll
+                for (int q4 = 0; q4 < K / 16; ++q4) kk[j][q4] = kr[q4];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                int s = 0;
+#pragma unroll
+                for (int q4 = 0; q4 < K / 16; ++q4) {
+                    s = __builtin_amdgcn_sdot4(qrow[4 * q4 + 0], kk[j][q4].x, s, false);
+                    s = __builtin_amdgcn_sdot4(qrow[4 * q4 + 1], kk[j][q4].y, s, false);
+                    s = __builtin_amdgcn_sdot4(qrow[4 * q4 + 2], kk[j][q4].z, s, false);
+                    s = __builtin_amdgcn_sdot4(qrow[4 * q4 + 3], kk[j][q4].w, s, false);
+                }
+                const bool valid = j0 + j < run && first + j0 + j < nc;
+                sc[j0 + j] = valid ? s : INT32_MIN;
+                top = max(top, sc[j0 + j]);
+            }
+        } else {
+#pragma unroll
+            for (int j = j0; j < j0 + 8; ++j) sc[j] = INT32_MIN;
+        }
+    }
+
+    // ---- select: exact threshold, all units at once ---------------------------------------------
+    int T;
+    {
+        // every candidate reaches T0 and there are at least keep of them
+        int lo = T0, hi = active ? max(unit_max(top), T0) : T0;
+        while (__ballot(lo < hi) != 0) {
+            const int mid = (lo + hi + 1) >> 1;
+            int cnt = 0;
+#pragma unroll
+            for (int j0 = 0; j0 < kStreamSlots; j0 += 8) {
+                if (j0 < run_max) {
+#pragma unroll
+                    for (int j = j0; j < j0 + 8; ++j) count_if_ge(cnt, sc[j], mid);
+                }
+            }
+            cnt = unit_sum(cnt);
+            const bool ge = cnt >= keep;
+            lo = ge ? mid : lo;
+            hi = ge ? hi : mid - 1;
+        }
+        T = lo;
+    }
+    // kept keys into the image of the index rows: position = kept candidates before this one
+    wave_lds_sync();          // the bitmap is dead from here on: `rows` takes its place
+    {
+        int gt = 0, eq = 0;
+#pragma unroll
+        for (int j0 = 0; j0 < kStreamSlots; j0 += 8) {
+            if (j0 < run_max) {
+#pragma unroll
+                for (int j = j0; j < j0 + 8; ++j) {
+                    gt += sc[j] > T;
+                    eq += sc[j] == T;
+                }
+            }
+        }
+        int gt_unit, eq_unit;
+        const int gt_before = unit_excl_scan(gt, g, &gt_unit);
+        int eq_run = unit_excl_scan(eq, g, &eq_unit);            // ties before this lane's run
+        const int need_eq = keep - gt_unit;                      // ties to keep, in key order
+        // kept before this lane's run: every greater score, and the ties that still fit
+        int pos = gt_before + min(eq_run, need_eq);
+#pragma unroll
+        for (int j0 = 0; j0 < kStreamSlots; j0 += 8) {
+            if (j0 < run_max) {
+                uint16_t key[8];           // all eight reads before the first write: one wait per group
+#pragma unroll
+                for (int j = 0; j < 8; ++j) key[j] = list[min(first + j0 + j, kStreamCap - 1)];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int s = sc[j0 + j];
+                    const bool is_eq = s == T;                   // T >= T0 > INT32_MIN: empty slots never match
+                    const bool take = s > T || (is_eq && eq_run < need_eq);
+                    // a slot that is not kept writes to the spare slot behind the rows
+                    rows[take && active ? c * keep + min(pos, keep - 1) : kStreamUnits * keep] = key[j];
+                    pos += take;
+                    eq_run += is_eq;
+                }
+            }
+        }
+    }
+    wave_lds_sync();
+    // the rows of this wavefront's units are contiguous in memory; rows of units that took the slow path
+    // were written there and are skipped
+    {
+        int32_t *out = idx + ((size_t)n * L + u0) * keep;
+        const unsigned fit_units = (unsigned)__ballot(fits && g == 0);      // bit = unit
+        for (int uu = 0; uu < nu; ++uu) {
+            if (!((fit_units >> uu) & 1u) || !task_live) continue;
+            for (int e = lane; e < keep; e += kWave) out[uu * keep + e] = (int)rows[uu * keep + e];
+        }
+    }
+}
+
+// LDS of one workgroup: per wavefront the bitmap (later the image of the index rows) and the lists.
+size_t stream_words_per_wave(const dsa_shape &sh)
+{
+    const size_t head_words =
+        std::max<size_t>((size_t)(stream_quarter(sh.L) / 32) * kWave, ((size_t)kStreamUnits * sh.keep + 2) / 2);
+    return head_words + (size_t)kStreamUnits * kStreamStride / 2;
+}
+size_t stream_lds_bytes(const dsa_shape &sh) { return sizeof(unsigned) * stream_words_per_wave(sh) * kStreamWaves; }
+
+template <int K, int NB>
+hipError_t launch_stream_t(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *idx, hipStream_t st)
+{
+    const size_t words_per_wave = stream_words_per_wave(sh);
+    const size_t lds = stream_lds_bytes(sh);
+    auto kern = predict_stream<K, NB>;
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
+    const int tasks_per_head = (sh.L + kStreamUnits - 1) / kStreamUnits;
+    const unsigned tasks = (unsigned)sh.B * sh.H * tasks_per_head;
+    hipLaunchKernelGGL(kern, dim3((tasks + kStreamWaves - 1) / kStreamWaves), dim3(kStreamWaves * kWave), lds, st, Qt, Kt,
+                       idx, sh.L, sh.keep, tasks_per_head, tasks, (int)words_per_wave);
+    return hipGetLastError();
+}
+
+// Buckets of a unit that hold at least one key, for NB maxima per lane.
+int stream_buckets(int L, int nb)
+{
+    const int Lq = stream_quarter(L);
+    int total = 0;
+    for (int q = 0; q < 4; ++q) {
+        const int nvalid = L - q * Lq < 0 ? 0 : (L - q * Lq > Lq ? Lq : L - q * Lq);
+        const int tiles = (nvalid + 3) / 4;
+        total += tiles < nb ? tiles : nb;
+    }
+    return total;
+}
+
+}  // namespace
+
+// Bucket maxima per lane for a sequence length: one round of buckets for short sequences, the
+// long-sequence count otherwise.
+int stream_nb(int L)
+{
+    const int tiles = stream_quarter(L) / 4;
+    return tiles <= 32 ? 32 : tiles <= 64 ? 64 : kStreamLongNB;
+}
+
+// The streaming kernel serves fine-grained masks whose bound can be tight: enough buckets for keep
+// (so that about 1.25 * keep candidates survive) and a candidate list that fits the register path.
+bool stream_predict_fits(const dsa_shape &sh)
+{
+    if (sh.vec != 1 || (sh.k != 16 && sh.k != 32 && sh.k != 64) || sh.L > kStreamMaxL) return false;
+    if (sh.keep > kStreamCap * 5 / 8) return false;     // about 1.25 * keep candidates, with room to spare
+    if (4 * stream_buckets(sh.L, stream_nb(sh.L)) < 5 * sh.keep) return false;
+    return stream_lds_bytes(sh) <= 160 * 1024;
+}
+
+template <int K>
+hipError_t launch_stream_k(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *idx, hipStream_t st)
+{
+    switch (stream_nb(sh.L)) {
+    case 32: return launch_stream_t<K, 32>(sh, Qt, Kt, idx, st);
+    case 64: return launch_stream_t<K, 64>(sh, Qt, Kt, idx, st);
+    default: return launch_stream_t<K, kStreamLongNB>(sh, Qt, Kt, idx, st);
+    }
+}
+
+hipError_t launch_predict_stream(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *idx,
+                                 hipStream_t st)
+{
+    if (sh.k == 16) return launch_stream_k<16>(sh, Qt, Kt, idx, st);
+    if (sh.k == 32) return launch_stream_k<32>(sh, Qt, Kt, idx, st);
+    return launch_stream_k<64>(sh, Qt, Kt, idx, st);
+}
+
+}  // namespace dsa

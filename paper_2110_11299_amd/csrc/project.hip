@@ -153,6 +153,9 @@ hipError_t launch_project_quantize(const dsa_shape &sh, int bits, const void *X,
     const size_t items = n / 4;
     const dim3 grid((unsigned)((items + kProjThreads - 1) / kProjThreads)), block(kProjThreads);
     const size_t lds = (size_t)sh.d * sh.k * sizeof(float);
+    const void *kern = sh.dtype == DSA_F32 ? reinterpret_cast<const void *>(project_rows<float>)
+                                           : reinterpret_cast<const void *>(project_rows<uint16_t>);
+    if (hipError_t e = allow_dynamic_lds(kern, lds)) return e;
     if (sh.dtype == DSA_F32)
         hipLaunchKernelGGL(project_rows<float>, grid, block, lds, st, static_cast<const float *>(X), R, Y, amax_bits,
                            rows, sh.d, sh.k);

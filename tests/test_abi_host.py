@@ -129,3 +129,13 @@ def test_noalloc_rejects_masks_beyond_its_array_on_the_host(b):
     st = lib.dsa_attention_fwd_noalloc(ctypes.byref(big), fake, fake, fake, fake, fake, fake, None)
     assert st == 5 and "workspace" in b.status_string(st)
     assert lib.dsa_attention_fwd_noalloc(ctypes.byref(big), None, fake, fake, fake, fake, fake, None) == 1
+
+
+def test_attention_rejects_lengths_whose_offsets_would_wrap(b):
+    """The attention kernels index a head with 32-bit element offsets: L above 2^22 is refused."""
+    lib = b.lib()
+    fake = ctypes.c_void_p(0x1000)
+    sh = good(b, B=1, H=1, L=(1 << 22) + 8, d=128, keep=8, vec=8)
+    assert lib.dsa_sddmm(ctypes.byref(sh), fake, fake, fake, fake, None) == 3
+    assert lib.dsa_spmm(ctypes.byref(sh), fake, fake, fake, fake, None) == 3
+    assert lib.dsa_masked_attention(ctypes.byref(sh), fake, fake, fake, fake, fake, None) == 3
