@@ -42,7 +42,7 @@ constexpr int kStreamCap = 4 * kStreamSlots;   // candidates of one unit (its fo
 constexpr int kStreamStride = kStreamCap + 2;  // list entries per unit in LDS: one spare slot, kept even
 constexpr int kStreamMaxL = 8192;       // bitmap of 16 units in LDS: 2 * L bytes per wavefront
 constexpr int kStreamPrefetch = 8;      // key tiles requested ahead of their use
-constexpr int kStreamWaves = 8;         // wavefronts (tasks) per workgroup: two per SIMD
+constexpr int kStreamWaves = 1;         // wavefronts (tasks) per workgroup (several share nothing but the launch)
 constexpr int kStreamLongNB = 128;      // bucket maxima per lane for long sequences
 
 // The key stream of one wavefront: scores of tile t (16 keys x 16 units) from v_mfma_i32_16x16x64_i8.
@@ -201,7 +201,7 @@ __device__ __forceinline__ int unit_excl_scan(int x, int g, int *total)
 // K is the projection dimension k (a template argument, so that the byte offsets of the key stream
 // are constants).
 template <int K, int NB>
-__global__ __launch_bounds__(kStreamWaves *kWave) void predict_stream(const int8_t *__restrict__ Qt,
+__global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const int8_t *__restrict__ Qt,
                                                            const int8_t *__restrict__ Kt,
                                                            int32_t *__restrict__ idx, int L, int keep,
                                                            int tasks_per_head, unsigned total_tasks,
@@ -216,10 +216,8 @@ __global__ __launch_bounds__(kStreamWaves *kWave) void predict_stream(const int8
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 15, g = lane >> 4;
     unsigned *smem = smem_all + wave * lds_words_per_wave;
-    // The wavefronts of a workgroup are independent (each has its own task and its own LDS) but start
-    // together on consecutive tasks of one head: they sweep the same keys at the same pace, so one
-    // compute unit's L1 serves most of their key requests.  A wavefront without a task mirrors the
-    // last one and writes nothing.
+    // The wavefronts of a workgroup are independent: each has its own task and its own LDS.  A wavefront
+    // without a task mirrors the last one and writes nothing.
     const unsigned slot = xcd_contiguous(blockIdx.x, gridDim.x) * kStreamWaves + wave;
     const bool task_live = slot < total_tasks;
     const unsigned task = task_live ? slot : total_tasks - 1;
@@ -300,7 +298,6 @@ __global__ __launch_bounds__(kStreamWaves *kWave) void predict_stream(const int8
     }
 
     // ---- pass 2: bitmap of candidates (score >= T0) ----------------------------------------------
-    __syncthreads();                             // start the second sweep together as well
     int mine = 0;                                // candidates in this lane's quarter
     {
         ks.restart();
