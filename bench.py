@@ -8,9 +8,12 @@ one vector-wise forward through dsa_attention_fwd (mask prediction, SDDMM, softm
 entries, SpMM), inputs resident in HBM.  value = heads*sequences processed per second over
 both passes.
 
-Prints ONE JSON line with the throughput, the roofline figures of the dominant kernel (the
-gather-bound attention kernel of the fine-grained pass) and the CPU oracle timed on the host
-cores on a bounded sample of the same workload.
+Prints ONE JSON line with the throughput, the roofline entry of the dominant kernel of the step
+(the fine-grained mask predictor: bound by plain vector-ALU work on the N*L*L approximate scores,
+with its int8 matrix-core rate beside it), a second entry for the fine-grained attention kernel
+against a gather roof measured in the same run (its K / V rows come from L2, so the HBM peak is not
+its roof), per-stage times of every workload configuration, and the CPU oracle timed on the host
+cores on the same workload.
 """
 from __future__ import annotations
 
@@ -30,11 +33,24 @@ INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 # plain vector ALU: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz = one 32-bit lane operation each
 ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 
-# HBM traffic of one launch of the dominant kernel (attention_rows at C4f), measured with two
-# rocprofv3 --pmc runs of `bench.py --pmc-mode` (FETCH_SIZE, then WRITE_SIZE), each scaled by what the
-# same counter reads for the 256 MiB calibration copy: profiles/bench_C4_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = 95.7e6
 PMC_COPY_BYTES = 256 << 20   # size of the calibration copy in --pmc-mode
+# HBM bytes per launch come from two rocprofv3 --pmc runs of `bench.py --pmc-mode` (FETCH_SIZE, then
+# WRITE_SIZE), each scaled by what the same counter reads for the calibration copy.  Their summary is a
+# tracked file; this run does not measure them, it quotes the row of the kernel it names (or null).
+TRAFFIC_SUMMARY = ROOT / "profiles" / "bench_C4_hbm_traffic.md"
+
+
+def profiled_traffic_bytes(kernel_prefix: str):
+    """Total HBM bytes per launch of the first kernel whose name starts with kernel_prefix in the
+    tracked FETCH_SIZE / WRITE_SIZE summary; None if the file or the row is missing."""
+    try:
+        for line in TRAFFIC_SUMMARY.read_text().splitlines():
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) == 6 and cells[0].strip("`").startswith(kernel_prefix):
+                return float(cells[5]) * 1e6
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def gather_bytes(cfg) -> int:
@@ -59,8 +75,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
-    ap.add_argument("--all-configs", action="store_true",
-                    help="also time every stage on the other workload configs (adds 'all_configs' to the line)")
+    ap.add_argument("--no-all-configs", action="store_true",
+                    help="skip timing every stage on the other workload configs ('all_configs' is then null)")
     ap.add_argument("--pmc-mode", action="store_true",
                     help="for rocprofv3 --pmc runs: a few steps plus one plain device copy of known size "
                          "(calibrates FETCH_SIZE / WRITE_SIZE), no other output")
@@ -106,6 +122,10 @@ def main() -> int:
     if args.pmc_mode:
         for _ in range(3):
             step()
+        rm = torch.empty((cf.B, cf.H, cf.L), dtype=torch.int32, device="cuda")
+        for _ in range(3):
+            pkg.dsa_approx_rowmax(passes[0]["sh"], Qt, Kt, rowmax=rm)
+        pkg.binding.dsa_gather_roof(passes[0]["sh"], K, V, passes[0]["idx"])
         src = torch.empty(PMC_COPY_BYTES, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
         dst.copy_(src)          # reads and writes PMC_COPY_BYTES each
@@ -148,9 +168,10 @@ def main() -> int:
             staged_softmax_ms=timed(lambda: pkg.dsa_sparse_softmax(shc, S, P=S), reps),
             staged_spmm_ms=timed(lambda: pkg.dsa_spmm(shc, S, ix, v, O=o), reps))
         st["heads_seqs_per_s"] = cfg.N / (st["fwd_ms"] * 1e-3)
+        # gathered (algorithmic) bytes are served by L2, not by HBM: a rate, not a fraction of the HBM peak
         st["attention_gather_GBs"] = gather_bytes(cfg) / (st["attention_ms"] * 1e-3) / 1e9
-        st["attention_frac_hbm"] = st["attention_gather_GBs"] / HBM_PEAK_GBS
         st["attention_compulsory_GBs"] = compulsory_bytes(cfg) / (st["attention_ms"] * 1e-3) / 1e9
+        st["attention_frac_hbm_compulsory"] = st["attention_compulsory_GBs"] / HBM_PEAK_GBS
         ops = 2.0 * cfg.N * cfg.L * cfg.L * cfg.k
         st["predict_int8_TOPS"] = ops / (st["predict_ms"] * 1e-3) / 1e12
         st["predict_frac_int8"] = st["predict_int8_TOPS"] / INT8_PEAK_TOPS
@@ -220,16 +241,41 @@ def main() -> int:
     copy_GBs = 2.0 * csrc.numel() / (copy_ms * 1e-3) / 1e9
     del csrc, cdst
 
+    # The dominant kernel of the step is the fine-grained predictor.  It is bound by plain vector-ALU
+    # work: every one of the N*L*L approximate scores has to be looked at once at least (the int8
+    # contraction that produces them is a small part of its time), so `achieved` counts one lane
+    # operation per score against the chip's 32-bit lane rate; the int8 rate is given beside it.
     dom = stages["C4f"]
-    roofline = dict(kernel="attention_rows (fine-grained SDDMM+softmax+SpMM)", bound="hbm",
-                    achieved=dom["attention_gather_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=dom["attention_frac_hbm"], traffic=MEASURED_TRAFFIC_BYTES,
-                    algorithmic_bytes=gather_bytes(cf), avg_launch_ms=dom["attention_ms"],
-                    compulsory_bytes=compulsory_bytes(cf), compulsory_GBs=dom["attention_compulsory_GBs"],
-                    device_copy_GBs=copy_GBs)
+    scores_per_launch = float(cf.N) * cf.L * cf.L
+    achieved_alu = scores_per_launch / (dom["predict_ms"] * 1e-3) / 1e12
+    roofline = dict(kernel="predict_stream<32, 128> (fine-grained dsa_predict_mask at C4: a1 + b)", bound="alu",
+                    achieved=achieved_alu, peak=ALU_PEAK_LANE_OPS / 1e12, unit="Tlane-op/s",
+                    frac=achieved_alu / (ALU_PEAK_LANE_OPS / 1e12),
+                    traffic=profiled_traffic_bytes("predict_stream<32, 128>"),
+                    traffic_source="profiles/bench_C4_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run)",
+                    algorithmic_ops=scores_per_launch, algorithmic_unit="score inspections (N*L*L), one lane operation each",
+                    avg_launch_ms=dom["predict_ms"], int8_TOPS=dom["predict_int8_TOPS"],
+                    frac_int8=dom["predict_frac_int8"], share_of_step=dom["predict_ms"] / ms_per_step)
+    # The fine-grained attention kernel gathers K / V rows that live in L2: its roof is the rate at which the
+    # memory hierarchy serves that access pattern, measured here with the gather-only twin of the kernel.
+    sink = torch.empty(cf.N * cf.L * 64, dtype=torch.int32, device="cuda")
+    gathered = pkg.binding.dsa_gather_roof(sh_f, K, V, passes[0]["idx"], sink)
+    gather_ms = timed(lambda: pkg.binding.dsa_gather_roof(sh_f, K, V, passes[0]["idx"], sink), reps)
+    roof_GBs = gathered / (gather_ms * 1e-3) / 1e9
+    kv_GBs = gathered / (dom["attention_ms"] * 1e-3) / 1e9
+    roofline_attention = dict(kernel="attention_rows<bf16, 64, fused> (fine-grained SDDMM+softmax+SpMM at C4: c1-c3)",
+                              bound="l2-gather", achieved=kv_GBs, peak=roof_GBs, unit="GB/s", frac=kv_GBs / roof_GBs,
+                              peak_source="dsa_gather_roof timed in this run: same launch shape and 16-byte gathers, no arithmetic",
+                              gathered_kv_bytes=gathered, gather_probe_ms=gather_ms, avg_launch_ms=dom["attention_ms"],
+                              algorithmic_bytes=gather_bytes(cf), compulsory_bytes=compulsory_bytes(cf),
+                              compulsory_GBs=dom["attention_compulsory_GBs"],
+                              frac_hbm_compulsory=dom["attention_compulsory_GBs"] / HBM_PEAK_GBS,
+                              traffic=profiled_traffic_bytes("attention_rows<unsigned short, 64, 0>"),
+                              device_copy_GBs=copy_GBs)
+    del sink
 
     all_configs = None
-    if args.all_configs:
+    if not args.no_all_configs:
         all_configs = {}
         for name in ("C1", "C2", "C3", "C5"):
             cfg = di.CONFIGS[name]
@@ -268,16 +314,18 @@ def main() -> int:
 
     out = dict(metric="DSA attn fwd heads*seqs/sec at L=4096, keep 5%", value=value, unit="heads*seqs/s",
                n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True,
-               scaling="weak", vs_baseline=None, dtype="f32",
+               scaling="weak", vs_baseline=None, dtype="bf16",
                data="synthetic",
                config=dict(workload="C4 long-sequence DSA: B=2 H=8 L=4096 d=64 bf16, k=32 int8, keep 205 (5%), "
                                     "one fine-grained pass + one vector-wise 8x1 pass per step",
-                           storage="Q,K,V bf16; Q~,K~ int8; O fp32", arithmetic="int8 x int8 -> int32 scores; "
-                           "fp32 dot products, softmax and accumulation",
+                           storage="Q,K,V bf16; Q~,K~ int8; idx int32; O fp32",
+                           arithmetic="int8 x int8 -> int32 approximate scores (exact); bf16 products with fp32 "
+                                      "accumulation for q.k and p.v (softmax weights rounded to bf16 for p.v); "
+                                      "softmax statistics in fp32",
                            heads_seqs_per_step=heads_seqs, seed=cf.seed),
-               roofline=roofline, cpu_baseline=cpu_baseline, stages=stages, contraction=contraction,
+               roofline=roofline, roofline_attention=roofline_attention, cpu_baseline=cpu_baseline, stages=stages, contraction=contraction,
                all_configs=all_configs,
-               low_precision_predict=dict(what="dsa_predict_mask_bits / dsa_attention_fwd_bits at C4 fine-grained (unpack to int8 + int8 path)",
+               low_precision_predict=dict(what="dsa_predict_mask_bits / dsa_attention_fwd_bits at C4 fine-grained",
                                           **low_precision),
                project_quantize=dict(what="Q~ and K~ from Q, K and R on the GPU (dsa_project_quantize twice), C4",
                                      ms=project_ms),

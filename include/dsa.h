@@ -176,6 +176,15 @@ dsa_status dsa_attention_fwd_bits(const dsa_shape *shape, int32_t bits, const vo
  * device) receives values of no meaning. */
 dsa_status dsa_mfma_i8_sustained(int32_t blocks, int32_t iters, int32_t *sink, void *stream);
 
+/* Measurement aid for steps (c1)-(c3): the gathers of the fine-grained attention kernel and nothing
+ * else (same launch shape, same key lists, the kept K rows and then the kept V rows of every query
+ * row read as 16-byte pieces, no arithmetic).  Timing it gives the rate at which the memory hierarchy
+ * serves this access pattern (K and V of a head are L2-resident at the workload sizes), the roof to
+ * set beside dsa_masked_attention; the HBM peak is not that roof.  `sink` (uint32 [B*H*L*64], device)
+ * receives values of no meaning. */
+dsa_status dsa_gather_roof(const dsa_shape *shape, const void *K, const void *V, const int32_t *idx,
+                           uint32_t *sink, void *stream);
+
 const char *dsa_status_string(dsa_status status);
 
 /* Library version, "major.minor". */

@@ -19,7 +19,7 @@ DSA_F32, DSA_BF16 = 0, 1
 EXPORTS = [
     "dsa_keep_from_ratio", "dsa_workspace_bytes", "dsa_predict_mask", "dsa_sddmm", "dsa_sparse_softmax",
     "dsa_spmm", "dsa_masked_attention", "dsa_attention_fwd", "dsa_attention_fwd_noalloc",
-    "dsa_noalloc_max_mask_bytes", "dsa_approx_rowmax", "dsa_mfma_i8_sustained",
+    "dsa_noalloc_max_mask_bytes", "dsa_approx_rowmax", "dsa_mfma_i8_sustained", "dsa_gather_roof",
     "dsa_project_quantize", "dsa_project_workspace_bytes",
     "dsa_project_quantize_bits", "dsa_predict_workspace_bytes_bits", "dsa_predict_mask_bits",
     "dsa_workspace_bytes_bits", "dsa_attention_fwd_bits",
@@ -91,6 +91,8 @@ def lib():
         L.dsa_attention_fwd_bits.argtypes = [shp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dsa_mfma_i8_sustained.restype = i32
         L.dsa_mfma_i8_sustained.argtypes = [i32, i32, vp, vp]
+        L.dsa_gather_roof.restype = i32
+        L.dsa_gather_roof.argtypes = [shp, vp, vp, vp, vp, vp]
         L.dsa_status_string.restype = ctypes.c_char_p
         L.dsa_status_string.argtypes = [i32]
         L.dsa_version.restype = ctypes.c_char_p
@@ -269,6 +271,19 @@ def dsa_mfma_i8_sustained(blocks: int, iters: int, sink=None):
     _dev(sink, torch.int32, (blocks * 256,))
     _check(lib().dsa_mfma_i8_sustained(blocks, iters, _ptr(sink), _stream()), "dsa_mfma_i8_sustained")
     return 4 * blocks * 4 * iters * 65536
+
+
+def dsa_gather_roof(shape, K, V, idx, sink=None):
+    """Launches the gather-only twin of the fine-grained attention kernel; returns the gathered bytes."""
+    import torch
+    tq, _, ti, _ = _dims(shape)
+    dt = _qkv_dtype(shape)
+    _dev(K, dt, tq); _dev(V, dt, tq); _dev(idx, torch.int32, ti)
+    n = shape.B * shape.H * shape.L * 64
+    sink = torch.empty(n, dtype=torch.int32, device=K.device) if sink is None else _dev(sink, torch.int32, (n,))
+    _check(lib().dsa_gather_roof(ctypes.byref(shape), _ptr(K), _ptr(V), _ptr(idx), _ptr(sink), _stream()),
+           "dsa_gather_roof")
+    return 2 * shape.B * shape.H * shape.L * shape.keep * shape.d * K.element_size()
 
 
 def dsa_project_quantize(shape, X, R, Xt=None, ws=None, want_amax=True):

@@ -281,6 +281,15 @@ dsa_status dsa_attention_fwd_bits(const dsa_shape *sh, int32_t bits, const void 
     return from_hip(dsa::launch_attention(dsa::kFused, *sh, Q, K, V, idx, nullptr, nullptr, O, (hipStream_t)stream));
 }
 
+dsa_status dsa_gather_roof(const dsa_shape *sh, const void *K, const void *V, const int32_t *idx, uint32_t *sink,
+                           void *stream)
+{
+    if (!sh || !K || !V || !idx || !sink) return DSA_ERR_NULL;
+    if (dsa_status s = check_attention(sh)) return s;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(idx) || !aligned16(sink)) return DSA_ERR_ALIGN;
+    return from_hip(dsa::launch_gather_probe(*sh, K, V, idx, sink, (hipStream_t)stream));
+}
+
 dsa_status dsa_mfma_i8_sustained(int32_t blocks, int32_t iters, int32_t *sink, void *stream)
 {
     if (!sink) return DSA_ERR_NULL;

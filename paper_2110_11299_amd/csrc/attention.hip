@@ -219,6 +219,49 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
     }
 }
 
+// Measurement aid: the gathers of attention_rows and nothing else.  Same launch shape, same key list
+// staged in LDS, same 16-byte pieces with four gathers in flight per lane, first over K and then over V;
+// the pieces are only folded into one word per row so that the loads cannot be dropped.  Its rate, in
+// gathered bytes per second, is the roof the memory hierarchy (L1 / L2, where K and V of a head live)
+// sets for this access pattern: the yardstick for attention_rows.
+template <typename T, int D>
+__global__ __launch_bounds__(kRowWaves *kWave) void gather_probe(const T *__restrict__ K, const T *__restrict__ V,
+                                                                 const int32_t *__restrict__ idx,
+                                                                 unsigned *__restrict__ sink, int L, int keep, int vec,
+                                                                 unsigned total_rows)
+{
+    typedef Piece<T> P;
+    constexpr int E = P::N, LPR = D / E, RPI = kWave / LPR, U = 4;
+    extern __shared__ float lds_scores[];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int sub = lane % LPR, grp = lane / LPR;
+    const unsigned row = xcd_contiguous(blockIdx.x, gridDim.x) * kRowWaves + wave;
+    const bool live = row < total_rows;
+    const unsigned r = live ? row : total_rows - 1;
+    const unsigned n = r / (unsigned)L, i = r % (unsigned)L;
+    const int32_t *list = idx + ((size_t)n * (L / vec) + i / vec) * keep;
+    int *sl = reinterpret_cast<int *>(lds_scores) + wave * keep;
+    for (int t = lane; t < keep; t += kWave) sl[t] = min(max(list[t], 0), L - 1);
+    wave_lds_fence();
+    unsigned acc = 0;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const T *Xh = (pass ? V : K) + (size_t)n * L * D;
+        for (int t0 = 0; t0 < keep; t0 += U * RPI) {
+            typename P::raw_t x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) x[u] = P::load(Xh + (unsigned)(sl[min(t0 + u * RPI + grp, keep - 1)] * D + sub * E));
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint4 w = __builtin_bit_cast(uint4, x[u]);
+                acc ^= (w.x ^ w.y) ^ (w.z ^ w.w);
+            }
+        }
+    }
+    if (live) sink[(size_t)r * kWave + lane] = acc;
+}
+
 // Group kernel for the vector-wise mask with bfloat16 inputs.  The 8 query rows of a group share
 // one key list, so each gathered key / value row serves 8 rows and the products become small
 // dense contractions for the bf16 matrix cores (v_mfma_f32_16x16x32_bf16, fp32 accumulate).  One
@@ -485,6 +528,25 @@ hipError_t launch_attention(AttnMode mode, const dsa_shape &sh, const void *Q, c
     }
     if (sh.d == 64) return launch_rows<uint16_t, 64>(mode, sh, Q, K, V, idx, Pin, S, O, st);
     return launch_rows<uint16_t, 128>(mode, sh, Q, K, V, idx, Pin, S, O, st);
+}
+
+hipError_t launch_gather_probe(const dsa_shape &sh, const void *K, const void *V, const int32_t *idx, unsigned *sink,
+                               hipStream_t st)
+{
+    const unsigned rows = (unsigned)sh.B * sh.H * sh.L;
+    const dim3 grid((rows + kRowWaves - 1) / kRowWaves), block(kRowWaves * kWave);
+    const size_t lds = (size_t)kRowWaves * sh.keep * sizeof(int);
+    auto go = [&](auto kern, auto *k, auto *v) -> hipError_t {
+        if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
+        hipLaunchKernelGGL(kern, grid, block, lds, st, k, v, idx, sink, sh.L, sh.keep, sh.vec, rows);
+        return hipGetLastError();
+    };
+    if (sh.dtype == DSA_F32) {
+        const float *k = static_cast<const float *>(K), *v = static_cast<const float *>(V);
+        return sh.d == 64 ? go(gather_probe<float, 64>, k, v) : go(gather_probe<float, 128>, k, v);
+    }
+    const uint16_t *k = static_cast<const uint16_t *>(K), *v = static_cast<const uint16_t *>(V);
+    return sh.d == 64 ? go(gather_probe<uint16_t, 64>, k, v) : go(gather_probe<uint16_t, 128>, k, v);
 }
 
 hipError_t launch_softmax(const dsa_shape &sh, const float *S, float *P, hipStream_t st)

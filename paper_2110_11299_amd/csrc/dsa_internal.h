@@ -60,6 +60,8 @@ enum AttnMode { kFused = 0, kSddmm = 1, kSpmm = 2 };
 hipError_t launch_attention(AttnMode mode, const dsa_shape &sh, const void *Q, const void *K,
                             const void *V, const int32_t *idx, const float *Pin, float *S, float *O,
                             hipStream_t st);
+hipError_t launch_gather_probe(const dsa_shape &sh, const void *K, const void *V, const int32_t *idx, unsigned *sink,
+                               hipStream_t st);
 hipError_t launch_softmax(const dsa_shape &sh, const float *S, float *P, hipStream_t st);
 hipError_t launch_rowmax(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *rowmax,
                          hipStream_t st);

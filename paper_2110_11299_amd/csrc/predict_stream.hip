@@ -315,10 +315,60 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
         }
     }
 
-    // ---- list: candidate keys of every unit in key order ----------------------------------------
+    // ---- ties: units whose candidates do not fit ---------------------------------------------------
+    // That is nearly always a plateau: very many keys share the score T0 (codes with few levels).  Such
+    // units are swept once more with the threshold T0 + 1; the words of that sweep (score > T0) go
+    // where the lists will be, and the bits that dropped out are the keys with score == T0.  If fewer
+    // than keep scores lie above T0 the answer is those keys plus the first ties in key order: the
+    // lane rewrites its words to exactly that set, and the unit goes on as one with keep candidates.
+    // If the strict candidates fit, the unit goes on with them and the bound T0 + 1.
     int nc;
+    int pos0 = unit_excl_scan(mine, g, &nc);
+    unsigned *gtmap = smem + head_words;         // [NWL][64], in the (still unused) list storage
+    const bool gt_fits = NWL * kWave * (int)sizeof(unsigned) <= kStreamUnits * kStreamStride * (int)sizeof(uint16_t);
+    if (gt_fits && __ballot(nc > kStreamCap && unit_live) != 0) {
+        const bool over = nc > kStreamCap && unit_live;
+        const int thr = over ? T0 + 1 : INT32_MAX;
+        int above = 0;
+        ks.restart();
+        for (int w = 0; w < NWL; ++w) {
+            unsigned word;
+            if (8 * w + 8 + 2 + PF <= tfull) {
+                word = pass2_word<false, K>(ks, 8 * w, thr);
+            } else {
+                word = pass2_word<true, K>(ks, 8 * w, thr);
+                const int nv = key_lim - (key_lo + 32 * w);
+                word = nv >= 32 ? word : nv <= 0 ? 0u : word & ((1u << nv) - 1u);
+            }
+            gtmap[w * kWave + lane] = word;
+            above += __popc(word);
+        }
+        int ngt;
+        unit_excl_scan(above, g, &ngt);
+        const bool ties = over && ngt < keep;
+        const bool strict = over && !ties && ngt <= kStreamCap;
+        int eq_unit;
+        const int eq_before = unit_excl_scan(mine - above, g, &eq_unit);
+        int quota = ties ? min(max(keep - ngt - eq_before, 0), mine - above) : 0;   // ties this lane keeps
+        if (ties || strict) {
+            mine = 0;
+            for (int w = 0; w < NWL; ++w) {
+                const unsigned gt = gtmap[w * kWave + lane];
+                const unsigned eq = bitmap[w * kWave + lane] & ~gt;
+                const unsigned kept_ties = lowest_set_bits(eq, quota);      // none for a strict unit
+                quota -= __popc(kept_ties);
+                const unsigned word = gt | kept_ties;
+                bitmap[w * kWave + lane] = word;
+                mine += __popc(word);
+            }
+            if (strict) T0 += 1;
+        }
+        pos0 = unit_excl_scan(mine, g, &nc);
+    }
+
+    // ---- list: candidate keys of every unit in key order ----------------------------------------
     {
-        int pos = unit_excl_scan(mine, g, &nc);
+        int pos = pos0;
         for (int w = 0; w < NWL; ++w) {
             unsigned m = bitmap[w * kWave + lane];          // this lane's own word: no fence needed
             // the wait for this read belongs here, once per word: left to the first use of m it would sit in
