@@ -437,3 +437,19 @@ def test_low_precision_mask_is_the_mask_of_the_codes(oracle, workload):
     assert np.array_equal(np.sort(order, axis=1), idx)
     kth = np.take_along_axis(S, order[:, -1:], axis=1)
     assert ((S == kth).sum(1) > 1).mean() > 0.5      # most rows have a tie at the threshold
+
+
+def test_column_locality_counts_on_a_hand_example():
+    """Figure 11's accounting on a case small enough to count by hand (section 5.2, table 4)."""
+    from oracle import column_locality as cl
+    # 4 elements, 3 kept keys each; key 7 is wanted by all, key 2 by two
+    tile = np.array([[1, 2, 7], [2, 5, 7], [0, 7, 9], [3, 4, 7]])
+    assert cl.fetches_in_order(tile) == 4 + 4 + 2          # steps: {1,2,0,3}, {2,5,7,4}, {7,9}
+    assert cl.fetches_union(tile) == 8                     # 0 1 2 3 4 5 7 9
+    g = cl.fetches_greedy(tile)
+    assert cl.fetches_union(tile) <= g <= 12               # feasible, never worse than row-by-row
+    assert g == 8                                          # 7 once for all four; 2 once for two; 0 3 | 1 5 9 4 alone
+    same = np.tile(np.arange(5), (8, 1))                   # identical lists: one fetch per step
+    assert cl.fetches_in_order(same) == 5 and cl.fetches_greedy(same) == 5 and cl.fetches_union(same) == 5
+    f = cl.reduction_factors(same, 1, 8)
+    assert f["in_order"] == 8.0 and f["reordered_greedy"] == 8.0 and f["reordered_floor"] == 8.0
