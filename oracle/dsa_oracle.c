@@ -314,3 +314,100 @@ int32_t dsao_unpack_codes(const uint8_t *packed, int64_t n, int32_t bits, int8_t
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Threshold masks (section 3.1: the mask may also be predicted "using thresholds", the threshold
+ * being a tuned constant).  The count per unit now varies, so the mask is stored in CSR form:
+ *   row_ptr int64 [n_units + 1], col int32 [row_ptr[n_units]], each unit's keys ascending.
+ * Step 3': unit u keeps every key j with score(u, j) >= theta (signed comparison of the exact
+ * integer scores of steps 1-2).  A unit with no such key keeps its single best key (largest score,
+ * lower index among equals): the softmax of its rows needs one entry, and that key is what a
+ * lowered threshold would have admitted first.
+ * With col == NULL only the counts are produced (row_ptr is filled); call again with col of
+ * row_ptr[n_units] entries to get the keys. */
+int32_t dsao_predict_mask_threshold(const int8_t *Qt, const int8_t *Kt, int32_t N, int32_t L, int32_t k,
+                                    int32_t vec, int64_t theta, int64_t *row_ptr, int32_t *col)
+{
+    if (!Qt || !Kt || !row_ptr || N < 1 || L < 1 || k < 1 || vec < 1 || L % vec) return 1;
+    const int64_t G = L / vec, n_units = (int64_t)N * G;
+    int failed = 0;
+    if (col == NULL) row_ptr[0] = 0;
+#pragma omp parallel
+    {
+        int64_t *sc = (int64_t *)malloc(sizeof(int64_t) * (size_t)L);
+        if (!sc) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t u = 0; u < n_units; ++u) {
+            if (!sc) continue;
+            unit_scores(Qt, Kt, L, k, vec, u / G, u % G, sc);
+            int64_t count = 0;
+            int32_t best = 0;
+            for (int32_t j = 0; j < L; ++j) {
+                if (sc[j] >= theta) {
+                    if (col) col[row_ptr[u] + count] = j;
+                    ++count;
+                }
+                if (sc[j] > sc[best]) best = j;          /* strict: the lower index wins among equals */
+            }
+            if (count == 0) {
+                if (col) col[row_ptr[u]] = best;
+                count = 1;
+            }
+            if (!col) row_ptr[u + 1] = count;            /* counts first; prefix sum below */
+        }
+        free(sc);
+    }
+    if (failed) return 1;
+    if (!col)
+        for (int64_t u = 0; u < n_units; ++u) row_ptr[u + 1] += row_ptr[u];
+    return 0;
+}
+
+/* Steps 4-6 for a CSR mask (the same equations 2, 4, 3, per row over its unit's keys) for the rows
+ * listed (all rows if rows == NULL): O [n_rows, d] in double. */
+int32_t dsao_masked_attention_csr(const float *Q, const float *K, const float *V, const int64_t *row_ptr,
+                                  const int32_t *col, int32_t N, int32_t L, int32_t d, int32_t vec,
+                                  double scale, const int64_t *rows, int64_t n_rows, double *O)
+{
+    if (!Q || !K || !V || !row_ptr || !col || !O || N < 1 || L < 1 || d < 1 || vec < 1 || L % vec) return 1;
+    const int64_t G = L / vec;
+    if (!rows) n_rows = (int64_t)N * L;
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t t = 0; t < n_rows; ++t) {
+        const int64_t r = rows ? rows[t] : t;
+        const int64_t n = r / L, i = r % L, u = n * G + i / vec;
+        const int32_t *list = col + row_ptr[u];
+        const int64_t cnt = row_ptr[u + 1] - row_ptr[u];
+        double *o = O + t * d;
+        for (int32_t c = 0; c < d; ++c) o[c] = 0.0;
+        if (cnt < 1) continue;                            /* cannot happen for masks made above */
+        double *p = (double *)malloc(sizeof(double) * (size_t)cnt);
+        if (!p) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
+        const float *q = Q + r * d;
+        double m = 0.0;
+        for (int64_t a = 0; a < cnt; ++a) {               /* equation 2 at the kept positions */
+            const float *kr = K + (n * L + list[a]) * (int64_t)d;
+            double acc = 0.0;
+            for (int32_t c = 0; c < d; ++c) acc += (double)q[c] * (double)kr[c];
+            p[a] = scale * acc;
+            if (a == 0 || p[a] > m) m = p[a];
+        }
+        double z = 0.0;
+        for (int64_t a = 0; a < cnt; ++a) { p[a] = exp(p[a] - m); z += p[a]; }     /* equation 4 */
+        for (int64_t a = 0; a < cnt; ++a) {               /* equation 3 */
+            const float *vr = V + (n * L + list[a]) * (int64_t)d;
+            const double w = p[a] / z;
+            for (int32_t c = 0; c < d; ++c) o[c] += w * (double)vr[c];
+        }
+        free(p);
+    }
+    return failed;
+}

@@ -57,6 +57,10 @@ def _load():
         lib.dsao_project_quantize.argtypes = [vp, vp, i64, i32, i32, vp, vp]
         lib.dsao_project_quantize_bits.restype = i32
         lib.dsao_project_quantize_bits.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
+        lib.dsao_predict_mask_threshold.restype = i32
+        lib.dsao_predict_mask_threshold.argtypes = [vp, vp, i32, i32, i32, i32, i64, vp, vp]
+        lib.dsao_masked_attention_csr.restype = i32
+        lib.dsao_masked_attention_csr.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f64, vp, i64, vp]
         lib.dsao_pack_codes.restype = i32
         lib.dsao_pack_codes.argtypes = [vp, i64, i32, vp]
         lib.dsao_unpack_codes.restype = i32
@@ -206,6 +210,38 @@ def attention_fwd(Q, K, V, Qt, Kt, keep, scale, vec=1):
     """Whole path, all rows.  Returns (O float64 [N*L, d], idx int32 [N*L/vec, keep])."""
     idx = predict_mask(Qt, Kt, keep, vec)
     return masked_attention(Q, K, V, idx, scale, vec), idx
+
+
+def predict_mask_threshold(Qt, Kt, theta, vec=1):
+    """Step 3' (threshold mask).  Returns (row_ptr int64 [n_units + 1], col int32 [nnz]): unit u keeps the keys
+    col[row_ptr[u]:row_ptr[u+1]], ascending: every key with score >= theta, or its single best key if none."""
+    Qt, Kt = _flat_heads(Qt, np.int8), _flat_heads(Kt, np.int8)
+    N, L, k = Qt.shape
+    assert Kt.shape == Qt.shape
+    row_ptr = np.zeros(N * (L // vec) + 1, dtype=np.int64)
+    if _load().dsao_predict_mask_threshold(_p(Qt), _p(Kt), N, L, k, vec, int(theta), _p(row_ptr), None):
+        raise ValueError("dsao_predict_mask_threshold: bad arguments")
+    col = np.empty(int(row_ptr[-1]), dtype=np.int32)
+    if _load().dsao_predict_mask_threshold(_p(Qt), _p(Kt), N, L, k, vec, int(theta), _p(row_ptr), _p(col)):
+        raise ValueError("dsao_predict_mask_threshold: bad arguments")
+    return row_ptr, col
+
+
+def masked_attention_csr(Q, K, V, row_ptr, col, scale, vec=1, rows=None):
+    """Steps 4-6 for a CSR mask.  float64 O [n_rows, d]."""
+    Q, K, V = (_flat_heads(x, np.float32) for x in (Q, K, V))
+    N, L, d = Q.shape
+    row_ptr = _arr(row_ptr, np.int64, 1)
+    col = _arr(col, np.int32, 1)
+    assert row_ptr.size == N * (L // vec) + 1 and row_ptr[-1] == col.size
+    r, nr = _sel(rows)
+    if r is None:
+        nr = N * L
+    O = np.empty((nr, d), dtype=np.float64)
+    if _load().dsao_masked_attention_csr(_p(Q), _p(K), _p(V), _p(row_ptr), _p(col), N, L, d, vec, float(scale),
+                                         _p(r), nr, _p(O)):
+        raise ValueError("dsao_masked_attention_csr: bad arguments")
+    return O
 
 
 def project_quantize(X, R, bits=8):

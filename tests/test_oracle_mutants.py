@@ -38,6 +38,12 @@ MUTANTS = [
     ("packed fields in the opposite order", "<< (bits * f);", "<< (bits * (per - 1 - f));"),
     ("unpacking without sign extension", "codes[j] = (int8_t)(((int32_t)field ^ sign) - sign);",
      "codes[j] = (int8_t)field; (void)sign;"),
+    ("threshold is strict", "if (sc[j] >= theta) {", "if (sc[j] > theta) {"),
+    ("empty unit keeps the highest index among equals", "if (sc[j] > sc[best]) best = j;", "if (sc[j] >= sc[best]) best = j;"),
+    ("empty unit keeps nothing", "if (count == 0) {\n                if (col) col[row_ptr[u]] = best;\n                count = 1;",
+     "if (count < 0) {\n                if (col) col[row_ptr[u]] = best;\n                count = 1;"),
+    ("CSR row reads the next unit's keys", "const int32_t *list = col + row_ptr[u];", "const int32_t *list = col + row_ptr[u] + 1;"),
+    ("CSR weights not normalised", "const double w = p[a] / z;", "const double w = p[a]; (void)z;"),
     ("projection matrix transposed", "y = fmaf(X[r * d + c], R[(int64_t)c * k + j], y);",
      "y = fmaf(X[r * d + c], R[(int64_t)(j % d) * k + (c % k)], y);"),
 ]

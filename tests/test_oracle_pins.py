@@ -453,3 +453,97 @@ def test_column_locality_counts_on_a_hand_example():
     assert cl.fetches_in_order(same) == 5 and cl.fetches_greedy(same) == 5 and cl.fetches_union(same) == 5
     f = cl.reduction_factors(same, 1, 8)
     assert f["in_order"] == 8.0 and f["reordered_greedy"] == 8.0 and f["reordered_floor"] == 8.0
+
+
+# ---------------------------------------------------------------- threshold masks (CSR)
+def python_threshold(scores, theta):
+    """Pure-Python statement of the threshold rule for one unit: every key at or above theta, ascending;
+    if there is none, the single best key (highest score, lowest index among equals)."""
+    kept = [j for j in range(len(scores)) if scores[j] >= theta]
+    if not kept:
+        best = 0
+        for j in range(1, len(scores)):
+            if scores[j] > scores[best]:
+                best = j
+        kept = [best]
+    return kept
+
+
+@pytest.mark.parametrize("vec,lo,hi", [(1, -127, 127), (1, -2, 2), (4, -5, 5), (8, -127, 127)])
+def test_threshold_mask_brute_force(oracle, vec, lo, hi):
+    # section 3.1: masks "using thresholds"; every theta from below every score to above every score
+    _, _, _, Qt, Kt = tiny(40 + vec, N=2, L=24, k=8, lo=lo, hi=hi)
+    sc = oracle.approx_scores(Qt, Kt, vec)
+    thetas = sorted(set(np.quantile(sc, [0, 0.2, 0.5, 0.9, 0.99, 1.0]).astype(np.int64).tolist()
+                        + [int(sc.min()) - 1, int(sc.max()) + 1, 0]))
+    for theta in thetas:
+        row_ptr, col = oracle.predict_mask_threshold(Qt, Kt, theta, vec)
+        assert row_ptr[0] == 0 and row_ptr.shape == (sc.shape[0] + 1,) and row_ptr[-1] == col.size
+        for u in range(sc.shape[0]):
+            assert col[row_ptr[u]:row_ptr[u + 1]].tolist() == python_threshold(sc[u].tolist(), theta), (theta, u)
+
+
+def test_threshold_empty_units_keep_their_best_key_lowest_index(oracle):
+    _, _, _, Qt, Kt = tiny(44, N=1, L=16, k=8, lo=-3, hi=3)
+    Kt[0, 5] = Kt[0, 2]                                  # equal scores for keys 2 and 5 in every unit
+    sc = oracle.approx_scores(Qt, Kt, 1)
+    row_ptr, col = oracle.predict_mask_threshold(Qt, Kt, int(sc.max()) + 1, 1)
+    assert (np.diff(row_ptr) == 1).all()
+    assert col.tolist() == [int(np.argmax(s)) for s in sc]          # argmax: first maximum
+    Qz = np.zeros_like(Qt)                               # all scores 0: key 0 for every unit
+    _, col0 = oracle.predict_mask_threshold(Qz, Kt, 1, 1)
+    assert (col0 == 0).all()
+
+
+def test_threshold_at_the_kth_score_is_the_topk_mask(oracle):
+    # with no tie at the cut, "score >= k-th largest score" is the top-k mask of section 3.1
+    _, _, _, Qt, Kt = tiny(45, N=1, L=32, k=8)
+    sc = oracle.approx_scores(Qt, Kt, 1)
+    keep = 6
+    for u in range(sc.shape[0]):
+        srt = np.sort(sc[u])[::-1]
+        if srt[keep - 1] == srt[keep]:
+            continue
+        row_ptr, col = oracle.predict_mask_threshold(Qt, Kt, int(srt[keep - 1]), 1)
+        want = oracle.predict_mask(Qt, Kt, keep, 1)[u]
+        assert col[row_ptr[u]:row_ptr[u + 1]].tolist() == want.tolist()
+
+
+@pytest.mark.parametrize("vec", [1, 8])
+def test_csr_attention_equals_additive_mask_form(oracle, vec):
+    # equation 4 with the mask scattered from the CSR lists, c = 1e4; counts differ from row to row
+    Q, K, V, Qt, Kt = tiny(46, N=2, L=32, d=8)
+    scale = np.float32(8 ** -0.5)
+    sc = oracle.approx_scores(Qt, Kt, vec)
+    theta = int(np.quantile(sc, 0.85))
+    row_ptr, col = oracle.predict_mask_threshold(Qt, Kt, theta, vec)
+    counts = np.diff(row_ptr)
+    assert counts.min() >= 1 and counts.max() > counts.min()
+    O = oracle.masked_attention_csr(Q, K, V, row_ptr, col, scale, vec)
+    G = 32 // vec
+    M = np.zeros((2, 32, 32))
+    for n in range(2):
+        for i in range(32):
+            u = n * G + i // vec
+            M[n, i, col[row_ptr[u]:row_ptr[u + 1]]] = 1.0
+    S = np.einsum("nic,njc->nij", Q.astype(np.float64), K.astype(np.float64)) * float(scale)
+    Sm = S - PAPER["mask_constant"] * (1.0 - M)
+    E = np.exp(Sm - Sm.max(axis=-1, keepdims=True))
+    A = E / E.sum(axis=-1, keepdims=True)
+    want = (A @ V.astype(np.float64)).reshape(64, 8)
+    assert np.abs(O - want).max() < 1e-12
+    # a subset of rows gives the same rows
+    rows = np.array([3, 17, 40, 63])
+    assert np.array_equal(oracle.masked_attention_csr(Q, K, V, row_ptr, col, scale, vec, rows=rows), O[rows])
+
+
+def test_csr_attention_with_equal_counts_is_the_ell_result(oracle):
+    Q, K, V, Qt, Kt = tiny(47, N=2, L=24, d=8)
+    scale, keep = np.float32(0.3), 5
+    idx = oracle.predict_mask(Qt, Kt, keep, 1)
+    row_ptr = np.arange(idx.shape[0] + 1, dtype=np.int64) * keep
+    O_csr = oracle.masked_attention_csr(Q, K, V, row_ptr, idx.reshape(-1), scale, 1)
+    assert np.abs(O_csr - oracle.masked_attention(Q, K, V, idx, scale, 1)).max() < 1e-15
+    # one key: the value row itself
+    one = oracle.masked_attention_csr(Q, K, V, np.arange(49, dtype=np.int64), idx[:, 0].copy(), scale, 1)
+    assert np.array_equal(one, V.reshape(48, 8)[np.arange(48) // 24 * 24 + idx[:, 0]].astype(np.float64))
