@@ -176,6 +176,27 @@ dsa_status dsa_attention_fwd_bits(const dsa_shape *shape, int32_t bits, const vo
  * device) receives values of no meaning. */
 dsa_status dsa_mfma_i8_sustained(int32_t blocks, int32_t iters, int32_t *sink, void *stream);
 
+/* Threshold masks (section 3.1: the mask M may be predicted from S~ "using thresholds" instead of a
+ * top-k search; the threshold is a tuned constant).  Steps (a)+(b) with the rule
+ *     unit u keeps key j  iff  S~[u, j] >= theta      (signed comparison of the exact integer scores),
+ * and a unit that no key satisfies keeps its single best key (largest score, lower index among
+ * equals), so that every row has a softmax.  The count per unit varies, so the mask is CSR:
+ *     row_ptr int32 [B*H*L/vec + 1], row_ptr[0] = 0;  col int32: unit u keeps col[row_ptr[u] .. row_ptr[u+1]),
+ *     ascending.  row_ptr[last] is the number of kept positions in all.
+ * `col` has room for col_capacity entries; entries beyond it are not written, and the caller sees
+ * from row_ptr[last] > col_capacity that it has to call again with a larger array.  shape->keep is
+ * not used (pass 1).  Built for vec = 1 and k = 16, 32 or 64 (others: DSA_ERR_UNSUPPORTED), and for
+ * B*H*L*L <= 2^31 - 1.  `ws`: device scratch of at least dsa_threshold_workspace_bytes(). */
+size_t dsa_threshold_workspace_bytes(const dsa_shape *shape);
+dsa_status dsa_predict_mask_threshold(const dsa_shape *shape, const int8_t *Qt, const int8_t *Kt, int32_t theta,
+                                      int32_t *row_ptr, int32_t *col, int64_t col_capacity, void *ws,
+                                      size_t ws_bytes, void *stream);
+
+/* Steps (c1)-(c3) in one kernel for a CSR mask (equations 2, 4, 3 per row over the keys of its unit;
+ * any count per unit, a unit without keys gives a zero row).  shape->keep is not used. */
+dsa_status dsa_masked_attention_csr(const dsa_shape *shape, const void *Q, const void *K, const void *V,
+                                    const int32_t *row_ptr, const int32_t *col, float *O, void *stream);
+
 /* Measurement aid for steps (c1)-(c3): the gathers of the fine-grained attention kernel and nothing
  * else (same launch shape, same key lists, the kept K rows and then the kept V rows of every query
  * row read as 16-byte pieces, no arithmetic).  Timing it gives the rate at which the memory hierarchy

@@ -20,6 +20,7 @@ EXPORTS = [
     "dsa_keep_from_ratio", "dsa_workspace_bytes", "dsa_predict_mask", "dsa_sddmm", "dsa_sparse_softmax",
     "dsa_spmm", "dsa_masked_attention", "dsa_attention_fwd", "dsa_attention_fwd_noalloc",
     "dsa_noalloc_max_mask_bytes", "dsa_approx_rowmax", "dsa_mfma_i8_sustained", "dsa_gather_roof",
+    "dsa_threshold_workspace_bytes", "dsa_predict_mask_threshold", "dsa_masked_attention_csr",
     "dsa_project_quantize", "dsa_project_workspace_bytes",
     "dsa_project_quantize_bits", "dsa_predict_workspace_bytes_bits", "dsa_predict_mask_bits",
     "dsa_workspace_bytes_bits", "dsa_attention_fwd_bits",
@@ -91,6 +92,12 @@ def lib():
         L.dsa_attention_fwd_bits.argtypes = [shp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dsa_mfma_i8_sustained.restype = i32
         L.dsa_mfma_i8_sustained.argtypes = [i32, i32, vp, vp]
+        L.dsa_threshold_workspace_bytes.restype = sz
+        L.dsa_threshold_workspace_bytes.argtypes = [shp]
+        L.dsa_predict_mask_threshold.restype = i32
+        L.dsa_predict_mask_threshold.argtypes = [shp, vp, vp, i32, vp, vp, ctypes.c_int64, vp, sz, vp]
+        L.dsa_masked_attention_csr.restype = i32
+        L.dsa_masked_attention_csr.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp]
         L.dsa_gather_roof.restype = i32
         L.dsa_gather_roof.argtypes = [shp, vp, vp, vp, vp, vp]
         L.dsa_status_string.restype = ctypes.c_char_p
@@ -271,6 +278,40 @@ def dsa_mfma_i8_sustained(blocks: int, iters: int, sink=None):
     _dev(sink, torch.int32, (blocks * 256,))
     _check(lib().dsa_mfma_i8_sustained(blocks, iters, _ptr(sink), _stream()), "dsa_mfma_i8_sustained")
     return 4 * blocks * 4 * iters * 65536
+
+
+def threshold_workspace_bytes(shape: DsaShape) -> int:
+    return int(lib().dsa_threshold_workspace_bytes(ctypes.byref(shape)))
+
+
+def dsa_predict_mask_threshold(shape, Qt, Kt, theta, col_capacity, row_ptr=None, col=None, ws=None):
+    """Threshold mask in CSR form.  Returns (row_ptr int32 [units + 1], col int32 [col_capacity]); the entries of
+    col beyond row_ptr[-1] are not written, and nothing beyond col_capacity is."""
+    import torch
+    _, tk, _, _ = _dims(shape)
+    _dev(Qt, torch.int8, tk); _dev(Kt, torch.int8, tk)
+    units = shape.B * shape.H * (shape.L // shape.vec)
+    row_ptr = torch.empty(units + 1, dtype=torch.int32, device=Qt.device) if row_ptr is None \
+        else _dev(row_ptr, torch.int32, (units + 1,))
+    col = torch.empty(max(col_capacity, 4), dtype=torch.int32, device=Qt.device) if col is None else col
+    if ws is None:
+        ws = torch.empty(max(threshold_workspace_bytes(shape), 16), dtype=torch.uint8, device=Qt.device)
+    _check(lib().dsa_predict_mask_threshold(ctypes.byref(shape), _ptr(Qt), _ptr(Kt), int(theta), _ptr(row_ptr), _ptr(col),
+                                            int(col_capacity), _ptr(ws), ws.numel(), _stream()),
+           "dsa_predict_mask_threshold")
+    return row_ptr, col
+
+
+def dsa_masked_attention_csr(shape, Q, K, V, row_ptr, col, O=None):
+    import torch
+    tq, _, _, _ = _dims(shape)
+    dt = _qkv_dtype(shape)
+    _dev(Q, dt, tq); _dev(K, dt, tq); _dev(V, dt, tq)
+    _dev(row_ptr, torch.int32, (shape.B * shape.H * (shape.L // shape.vec) + 1,))
+    O = torch.empty(tq, dtype=torch.float32, device=Q.device) if O is None else _dev(O, torch.float32, tq)
+    _check(lib().dsa_masked_attention_csr(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(row_ptr), _ptr(col),
+                                          _ptr(O), _stream()), "dsa_masked_attention_csr")
+    return O
 
 
 def dsa_gather_roof(shape, K, V, idx, sink=None):

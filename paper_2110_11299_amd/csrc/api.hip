@@ -281,6 +281,39 @@ dsa_status dsa_attention_fwd_bits(const dsa_shape *sh, int32_t bits, const void 
     return from_hip(dsa::launch_attention(dsa::kFused, *sh, Q, K, V, idx, nullptr, nullptr, O, (hipStream_t)stream));
 }
 
+size_t dsa_threshold_workspace_bytes(const dsa_shape *sh)
+{
+    if (check_predict(sh) != DSA_OK || !dsa::threshold_supported(*sh)) return 0;
+    return round_up_256(dsa::threshold_workspace_bytes(*sh));
+}
+
+dsa_status dsa_predict_mask_threshold(const dsa_shape *sh, const int8_t *Qt, const int8_t *Kt, int32_t theta,
+                                      int32_t *row_ptr, int32_t *col, int64_t col_capacity, void *ws,
+                                      size_t ws_bytes, void *stream)
+{
+    if (!sh || !Qt || !Kt || !row_ptr || !col || !ws) return DSA_ERR_NULL;
+    if (dsa_status s = check_predict(sh)) return s;
+    if (!dsa::threshold_supported(*sh)) return DSA_ERR_UNSUPPORTED;
+    // row_ptr is 32-bit: the largest possible mask (every key of every unit) has to fit
+    if ((int64_t)sh->B * sh->H * sh->L * sh->L > INT32_MAX) return DSA_ERR_UNSUPPORTED;
+    if (col_capacity < 0 || col_capacity > INT32_MAX) return DSA_ERR_SHAPE;
+    if (!aligned16(Qt) || !aligned16(Kt) || !aligned16(row_ptr) || !aligned16(col) || !aligned16(ws))
+        return DSA_ERR_ALIGN;
+    if (ws_bytes < dsa_threshold_workspace_bytes(sh)) return DSA_ERR_WORKSPACE;
+    return from_hip(dsa::launch_predict_threshold(*sh, Qt, Kt, theta, row_ptr, col, col_capacity, ws,
+                                                  (hipStream_t)stream));
+}
+
+dsa_status dsa_masked_attention_csr(const dsa_shape *sh, const void *Q, const void *K, const void *V,
+                                    const int32_t *row_ptr, const int32_t *col, float *O, void *stream)
+{
+    if (!sh || !Q || !K || !V || !row_ptr || !col || !O) return DSA_ERR_NULL;
+    if (dsa_status s = check_attention(sh)) return s;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(row_ptr) || !aligned16(col) || !aligned16(O))
+        return DSA_ERR_ALIGN;
+    return from_hip(dsa::launch_attention_csr(*sh, Q, K, V, row_ptr, col, O, (hipStream_t)stream));
+}
+
 dsa_status dsa_gather_roof(const dsa_shape *sh, const void *K, const void *V, const int32_t *idx, uint32_t *sink,
                            void *stream)
 {

@@ -219,6 +219,98 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
     }
 }
 
+// Row kernel for masks in CSR form (threshold masks, section 3.1: the count per row varies).  Same
+// wavefront-per-row scheme as attention_rows, fused only; a row's list is taken in chunks of
+// kCsrChunk keys with a running maximum, so that any count fits the same LDS: when a later chunk
+// raises the maximum, the sums so far are rescaled by exp(m_old - m_new).
+constexpr int kCsrChunk = 1024;
+
+template <typename T, int D>
+__global__ __launch_bounds__(kRowWaves *kWave) void attention_rows_csr(
+    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
+    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col, float *__restrict__ O, int L, int vec,
+    float scale, unsigned total_rows)
+{
+    typedef Piece<T> P;
+    constexpr int E = P::N, LPR = D / E, RPI = kWave / LPR, U = 4;
+    __shared__ int lists[kRowWaves][kCsrChunk];
+    __shared__ float scores[kRowWaves][kCsrChunk];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int sub = lane % LPR, grp = lane / LPR;
+    const unsigned row = xcd_contiguous(blockIdx.x, gridDim.x) * kRowWaves + wave;
+    if (row >= total_rows) return;                        // the whole wavefront: nothing below is shared
+    const unsigned n = row / (unsigned)L, i = row % (unsigned)L;
+    const size_t u = (size_t)n * (L / vec) + i / vec;
+    const int beg = row_ptr[u];
+    const int cnt = max(row_ptr[u + 1] - beg, 0);
+    int *sl = lists[wave];
+    float *sc = scores[wave];
+    const typename P::raw_t q = P::load(Q + (size_t)row * D + sub * E);
+    const T *Kh = K + (size_t)n * L * D, *Vh = V + (size_t)n * L * D;
+
+    float m = -INFINITY, z = 0.f, o[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) o[e] = 0.f;
+    for (int c0 = 0; c0 < cnt; c0 += kCsrChunk) {
+        const int nk = min(kCsrChunk, cnt - c0);
+        for (int t = lane; t < nk; t += kWave) sl[t] = min(max(col[beg + c0 + t], 0), L - 1);
+        wave_lds_fence();
+        float mc = -INFINITY;
+        for (int t0 = 0; t0 < nk; t0 += U * RPI) {
+            typename P::raw_t kv[U];
+#pragma unroll
+            for (int x = 0; x < U; ++x) kv[x] = P::load(Kh + (unsigned)(sl[min(t0 + x * RPI + grp, nk - 1)] * D + sub * E));
+#pragma unroll
+            for (int x = 0; x < U; ++x) {
+                const int t = t0 + x * RPI + grp;
+                const float acc = piece_sum<LPR>(P::dot(q, kv[x])) * scale;
+                if (t < nk) {
+                    mc = fmaxf(mc, acc);
+                    if (sub == 0) sc[t] = acc;
+                }
+            }
+        }
+        mc = groups_max<LPR>(mc);
+        const float m_new = fmaxf(m, mc);
+        const float f = __expf(m - m_new);               // 0 for the first chunk (m = -inf)
+        z *= f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[e] *= f;
+        m = m_new;
+        wave_lds_fence();
+        for (int t = lane; t < nk; t += kWave) sc[t] = __expf(sc[t] - m);
+        wave_lds_fence();
+        for (int t0 = 0; t0 < nk; t0 += U * RPI) {
+            typename P::raw_t vv[U];
+            float p[U];
+#pragma unroll
+            for (int x = 0; x < U; ++x) {
+                const int t = t0 + x * RPI + grp;
+                const int tt = min(t, nk - 1);
+                vv[x] = P::load(Vh + (unsigned)(sl[tt] * D + sub * E));
+                p[x] = t < nk ? sc[tt] : 0.f;
+            }
+#pragma unroll
+            for (int x = 0; x < U; ++x) {
+                z += p[x];
+                P::axpy(o, p[x], vv[x]);
+            }
+        }
+        wave_lds_fence();                                  // the next chunk overwrites list and scores
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e) o[e] = groups_sum<LPR>(o[e]);
+    z = groups_sum<LPR>(z);
+    const float inv = cnt > 0 ? 1.f / z : 0.f;            // a row without keys (not made by the predictor) gives 0
+    if (grp == 0) {
+        float *out = O + (size_t)row * D + sub * E;
+#pragma unroll
+        for (int e = 0; e < E; e += 4)
+            *reinterpret_cast<float4 *>(out + e) = make_float4(o[e] * inv, o[e + 1] * inv, o[e + 2] * inv, o[e + 3] * inv);
+    }
+}
+
 // Measurement aid: the gathers of attention_rows and nothing else.  Same launch shape, same key list
 // staged in LDS, same 16-byte pieces with four gathers in flight per lane, first over K and then over V;
 // the pieces are only folded into one word per row so that the loads cannot be dropped.  Its rate, in
@@ -528,6 +620,24 @@ hipError_t launch_attention(AttnMode mode, const dsa_shape &sh, const void *Q, c
     }
     if (sh.d == 64) return launch_rows<uint16_t, 64>(mode, sh, Q, K, V, idx, Pin, S, O, st);
     return launch_rows<uint16_t, 128>(mode, sh, Q, K, V, idx, Pin, S, O, st);
+}
+
+hipError_t launch_attention_csr(const dsa_shape &sh, const void *Q, const void *K, const void *V,
+                                const int32_t *row_ptr, const int32_t *col, float *O, hipStream_t st)
+{
+    const unsigned rows = (unsigned)sh.B * sh.H * sh.L;
+    const dim3 grid((rows + kRowWaves - 1) / kRowWaves), block(kRowWaves * kWave);
+    auto go = [&](auto kern, auto *q, auto *k, auto *v) -> hipError_t {
+        hipLaunchKernelGGL(kern, grid, block, 0, st, q, k, v, row_ptr, col, O, sh.L, sh.vec, sh.scale, rows);
+        return hipGetLastError();
+    };
+    if (sh.dtype == DSA_F32) {
+        const float *q = static_cast<const float *>(Q), *k = static_cast<const float *>(K), *v = static_cast<const float *>(V);
+        return sh.d == 64 ? go(attention_rows_csr<float, 64>, q, k, v) : go(attention_rows_csr<float, 128>, q, k, v);
+    }
+    const uint16_t *q = static_cast<const uint16_t *>(Q), *k = static_cast<const uint16_t *>(K),
+                   *v = static_cast<const uint16_t *>(V);
+    return sh.d == 64 ? go(attention_rows_csr<uint16_t, 64>, q, k, v) : go(attention_rows_csr<uint16_t, 128>, q, k, v);
 }
 
 hipError_t launch_gather_probe(const dsa_shape &sh, const void *K, const void *V, const int32_t *idx, unsigned *sink,

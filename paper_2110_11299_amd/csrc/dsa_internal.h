@@ -60,6 +60,13 @@ enum AttnMode { kFused = 0, kSddmm = 1, kSpmm = 2 };
 hipError_t launch_attention(AttnMode mode, const dsa_shape &sh, const void *Q, const void *K,
                             const void *V, const int32_t *idx, const float *Pin, float *S, float *O,
                             hipStream_t st);
+hipError_t launch_attention_csr(const dsa_shape &sh, const void *Q, const void *K, const void *V,
+                                const int32_t *row_ptr, const int32_t *col, float *O, hipStream_t st);
+// Threshold masks in CSR form: which shapes, how much scratch, the launch.
+bool threshold_supported(const dsa_shape &sh);
+size_t threshold_workspace_bytes(const dsa_shape &sh);
+hipError_t launch_predict_threshold(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int theta,
+                                    int32_t *row_ptr, int32_t *col, long long col_capacity, void *ws, hipStream_t st);
 hipError_t launch_gather_probe(const dsa_shape &sh, const void *K, const void *V, const int32_t *idx, unsigned *sink,
                                hipStream_t st);
 hipError_t launch_softmax(const dsa_shape &sh, const float *S, float *P, hipStream_t st);
