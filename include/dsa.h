@@ -28,12 +28,12 @@
  *        Qt, Kt    [B, H, L, k]   int8, the quantised projections Q~, K~
  *        idx       [B, H, L/vec, keep]  int32: the mask in ELL form.  Entry (b,h,u,:) lists,
  *                  ascending, the kept key positions of selection unit u: query row u when
- *                  vec = 1, query rows [vec*u, vec*u+vec) when vec = 8 (they share a list).
+ *                  vec = 1, query rows [vec*u, vec*u+vec) when vec = 4 or 8 (they share a list).
  *        S, P      [B, H, L, keep]  float: exact scores / attention weights at the kept
  *                  positions of each query row, in the order of its unit's list
  *        O         [B, H, L, d]   float
  *  - Selection rule (b): unit u keeps the `keep` keys j with the largest score, where the
- *    score is S~[u, j] (vec = 1) or the sum of S~[i, j] over the unit's vec rows (vec = 8),
+ *    score is S~[u, j] (vec = 1) or the sum of S~[i, j] over the unit's vec rows (vec = 4, 8),
  *    compared as signed integers; among equal scores the lower j wins.  The result is unique,
  *    so idx is reproducible bit for bit.
  *  - Argument checking happens on the host before anything is launched; a call that returns
@@ -70,7 +70,8 @@ typedef struct {
     int32_t d;      /* head dimension of Q, K, V: 64 or 128                                   */
     int32_t k;      /* projection dimension of Qt, Kt: a multiple of 16, 16 <= k <= 128       */
     int32_t keep;   /* kept keys per selection unit, 1 <= keep <= L (attention: <= 4096)      */
-    int32_t vec;    /* mask granularity in query rows: 1 (fine-grained) or 8 (vector-wise)    */
+    int32_t vec;    /* mask granularity in query rows: 1 (fine-grained), 4 or 8 (vector-wise: */
+                    /* the 1x4 and 1x8 column vectors of section 5.1, table 3)                */
     int32_t dtype;  /* dsa_dtype of Q, K, V                                                   */
     float scale;    /* factor on the exact scores before softmax; 1/sqrt(d) in equation 2     */
 } dsa_shape;

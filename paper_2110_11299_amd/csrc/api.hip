@@ -41,7 +41,7 @@ dsa_status check_common(const dsa_shape *sh)
     if (!sh) return DSA_ERR_NULL;
     if (sh->B < 1 || sh->H < 1 || sh->L < 1) return DSA_ERR_SHAPE;
     if ((int64_t)sh->B * sh->H > (1 << 24)) return DSA_ERR_SHAPE;
-    if (sh->vec != 1 && sh->vec != 8) return DSA_ERR_UNSUPPORTED;
+    if (sh->vec != 1 && sh->vec != 4 && sh->vec != 8) return DSA_ERR_UNSUPPORTED;
     if (sh->L % sh->vec) return DSA_ERR_SHAPE;
     if (sh->keep < 1 || sh->keep > sh->L) return DSA_ERR_SHAPE;
     if ((int64_t)sh->B * sh->H * sh->L > (int64_t)1 << 31) return DSA_ERR_UNSUPPORTED;

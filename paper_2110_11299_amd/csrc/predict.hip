@@ -865,16 +865,14 @@ hipError_t launch_predict(const dsa_shape &sh, const int8_t *Qt, const int8_t *K
     if (plan.ok) return launch_tiles(plan, sh, Qt, Kt, idx, st);
     const unsigned units = (unsigned)sh.B * sh.H * (sh.L / sh.vec);
     const size_t lds = ((size_t)sh.L + sh.vec * (sh.k / 4) + 8) * sizeof(int);
-    if (sh.vec == 1) {
-        auto kern = predict_unit<1>;
+    auto go = [&](auto kern) -> hipError_t {
         if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
         hipLaunchKernelGGL(kern, dim3(units), dim3(kUnitThreads), lds, st, Qt, Kt, idx, sh.L, sh.k, sh.keep);
-    } else {
-        auto kern = predict_unit<8>;
-        if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
-        hipLaunchKernelGGL(kern, dim3(units), dim3(kUnitThreads), lds, st, Qt, Kt, idx, sh.L, sh.k, sh.keep);
-    }
-    return hipGetLastError();
+        return hipGetLastError();
+    };
+    if (sh.vec == 1) return go(predict_unit<1>);
+    if (sh.vec == 4) return go(predict_unit<4>);
+    return go(predict_unit<8>);
 }
 
 // Nothing but v_mfma_i32_32x32x32_i8: four independent accumulation chains per wavefront, no memory

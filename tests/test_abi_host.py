@@ -76,7 +76,7 @@ def test_argument_errors_come_back_as_status_codes(b):
     assert lib.dsa_predict_mask(ref(good(b)), None, P, P, P, big, None) == OK_NULL
     assert lib.dsa_predict_mask(ref(good(b)), P, P, None, P, big, None) == OK_NULL
     for bad, want in [(dict(B=0), SHAPE), (dict(L=0), SHAPE), (dict(keep=0), SHAPE), (dict(keep=257), SHAPE),
-                      (dict(vec=8, L=252), SHAPE), (dict(vec=4), UNSUP), (dict(k=8), UNSUP), (dict(k=40), UNSUP),
+                      (dict(vec=8, L=252), SHAPE), (dict(vec=2), UNSUP), (dict(k=8), UNSUP), (dict(k=40), UNSUP),
                       (dict(k=256), UNSUP), (dict(L=1 << 20, keep=5), UNSUP)]:
         assert lib.dsa_predict_mask(ref(good(b, **bad)), P, P, P, P, big, None) == want, bad
     assert lib.dsa_predict_mask(ref(good(b)), P + 4, P, P, P, big, None) == ALIGN

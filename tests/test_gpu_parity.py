@@ -117,6 +117,11 @@ EDGE = [
     dict(B=1, H=1, L=12288, d=128, dtype="bf16", k=64, vec=8, keep=600),
     dict(B=2, H=1, L=328, d=64, dtype="f32", k=80, vec=8, keep=33),
     dict(B=1, H=1, L=3000, d=64, dtype="f32", k=112, vec=1, keep=300),
+    # 1x4 column vectors (section 5.1, table 3): groups of four query rows share a list
+    dict(B=2, H=2, L=2048, d=64, dtype="bf16", k=32, vec=4, keep=102, n_global=8),
+    dict(B=1, H=3, L=100, d=64, dtype="f32", k=16, vec=4, keep=9),
+    dict(B=1, H=1, L=6000, d=128, dtype="bf16", k=64, vec=4, keep=75),
+    dict(B=1, H=2, L=1000, d=64, dtype="f32", k=48, vec=4, keep=1),
 ]
 
 
@@ -126,7 +131,7 @@ def test_edge_shapes(dsa, oracle, spec):
     check_path(dsa, oracle, di.make_inputs(cfg), staged=True, label="edge")
 
 
-@pytest.mark.parametrize("vec", [1, 8])
+@pytest.mark.parametrize("vec", [1, 4, 8])
 @pytest.mark.parametrize("lo,hi", [(0, 0), (-1, 1), (-3, 3), (-127, 127)])
 def test_mask_with_heavy_ties(dsa, oracle, vec, lo, hi):
     """Narrow int8 ranges make most scores collide, so the lowest-index rule decides
@@ -413,7 +418,7 @@ def test_errors_launch_nothing(dsa):
     with pytest.raises(dsa.DsaError) as e:
         dsa.dsa_predict_mask(sh, Qt, Qt)
     assert e.value.status == 2
-    sh = dsa.make_shape(1, 1, 64, 64, 16, 8, 4, dsa.DSA_F32, 0.125)       # vec = 4
+    sh = dsa.make_shape(1, 1, 64, 64, 16, 8, 2, dsa.DSA_F32, 0.125)       # vec = 2
     with pytest.raises(dsa.DsaError) as e:
         dsa.dsa_predict_mask(sh, Qt, Qt)
     assert e.value.status == 3
