@@ -411,3 +411,44 @@ int32_t dsao_masked_attention_csr(const float *Q, const float *K, const float *V
     }
     return failed;
 }
+
+/* Step 0 with the paper's own projection (section 3.1, equation 5): P in sqrt(3/k) * {-1, 0, 1}^(d x k),
+ * a sparse random projection, so Y = X P needs additions and subtractions only.  P3 holds the signs
+ * (-1, 0, 1).  The constant sqrt(3/k) > 0 multiplies every entry of Y and the quantiser's scale
+ * qmax / max|Y| divides it out again, so it is left out; as for the dense projection the sums are
+ * taken in fp32 in increasing c (one rounding per addition), because a rounding decides a code. */
+int32_t dsao_project_quantize_ternary(const float *X, const int8_t *P3, int64_t rows, int32_t d, int32_t k,
+                                      int32_t bits, int8_t *Xt, float *amax_out)
+{
+    if (!X || !P3 || !Xt || rows < 0 || d < 1 || k < 1 || bits < 2 || bits > 8) return 1;
+    for (int64_t t = 0; t < (int64_t)d * k; ++t)
+        if (P3[t] < -1 || P3[t] > 1) return 2;
+    const float qmax = (float)((1 << (bits - 1)) - 1);
+    float *Y = (float *)malloc(sizeof(float) * (size_t)rows * (size_t)k + 4);
+    if (!Y) return 1;
+    float amax = 0.0f;
+#pragma omp parallel for schedule(static) reduction(max : amax)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int32_t j = 0; j < k; ++j) {
+            float y = 0.0f;
+            for (int32_t c = 0; c < d; ++c) {
+                const int8_t sign = P3[(int64_t)c * k + j];
+                if (sign > 0) y = y + X[r * d + c];
+                else if (sign < 0) y = y - X[r * d + c];
+            }
+            Y[r * k + j] = y;
+            if (fabsf(y) > amax) amax = fabsf(y);
+        }
+    }
+    const float s = amax > 0.0f ? qmax / amax : 0.0f;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < rows * (int64_t)k; ++t) {
+        float v = rintf(Y[t] * s);
+        if (v > qmax) v = qmax;
+        if (v < -qmax) v = -qmax;
+        Xt[t] = (int8_t)v;
+    }
+    if (amax_out) *amax_out = amax;
+    free(Y);
+    return 0;
+}

@@ -61,6 +61,8 @@ def _load():
         lib.dsao_predict_mask_threshold.argtypes = [vp, vp, i32, i32, i32, i32, i64, vp, vp]
         lib.dsao_masked_attention_csr.restype = i32
         lib.dsao_masked_attention_csr.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f64, vp, i64, vp]
+        lib.dsao_project_quantize_ternary.restype = i32
+        lib.dsao_project_quantize_ternary.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
         lib.dsao_pack_codes.restype = i32
         lib.dsao_pack_codes.argtypes = [vp, i64, i32, vp]
         lib.dsao_unpack_codes.restype = i32
@@ -259,6 +261,22 @@ def project_quantize(X, R, bits=8):
     if rc:
         raise ValueError("dsao_project_quantize_bits: bad arguments")
     return out, np.float32(amax[0])
+
+
+def project_quantize_ternary(X, P3, bits=8):
+    """Step 0 with a ternary projection (equation 5).  X [..., d] float32, P3 [d, k] int8 in {-1, 0, 1}.
+    Returns (codes int8 [..., k], amax)."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    P3 = _arr(P3, np.int8, 2)
+    d, k = P3.shape
+    assert X.shape[-1] == d
+    rows = X.size // d
+    Xt = np.empty(X.shape[:-1] + (k,), dtype=np.int8)
+    amax = np.zeros(1, dtype=np.float32)
+    rc = _load().dsao_project_quantize_ternary(_p(X), _p(P3), rows, d, k, bits, _p(Xt), _p(amax))
+    if rc:
+        raise ValueError("dsao_project_quantize_ternary: bad arguments" if rc == 1 else "P3 has entries outside {-1, 0, 1}")
+    return Xt, float(amax[0])
 
 
 def pack_codes(codes, bits):

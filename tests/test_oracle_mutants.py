@@ -44,6 +44,7 @@ MUTANTS = [
      "if (count < 0) {\n                if (col) col[row_ptr[u]] = best;\n                count = 1;"),
     ("CSR row reads the next unit's keys", "const int32_t *list = col + row_ptr[u];", "const int32_t *list = col + row_ptr[u] + 1;"),
     ("CSR weights not normalised", "const double w = p[a] / z;", "const double w = p[a]; (void)z;"),
+    ("ternary projection ignores the minus signs", "else if (sign < 0) y = y - X[r * d + c];", "else if (sign < 0) y = y + X[r * d + c];"),
     ("projection matrix transposed", "y = fmaf(X[r * d + c], R[(int64_t)c * k + j], y);",
      "y = fmaf(X[r * d + c], R[(int64_t)(j % d) * k + (c % k)], y);"),
 ]

@@ -547,3 +547,39 @@ def test_csr_attention_with_equal_counts_is_the_ell_result(oracle):
     # one key: the value row itself
     one = oracle.masked_attention_csr(Q, K, V, np.arange(49, dtype=np.int64), idx[:, 0].copy(), scale, 1)
     assert np.array_equal(one, V.reshape(48, 8)[np.arange(48) // 24 * 24 + idx[:, 0]].astype(np.float64))
+
+
+# ---------------------------------------------------------------- ternary projection (equation 5)
+def test_ternary_projection_closed_forms_and_dense_equivalent(oracle):
+    rng = np.random.default_rng(50)
+    d, k, rows = 12, 8, 40
+    X = rng.standard_normal((rows, d)).astype(np.float32)
+    # the usual sparse random projection: -1, 0, 1 with probabilities 1/6, 2/3, 1/6
+    P3 = rng.choice(np.array([-1, 0, 1], dtype=np.int8), size=(d, k), p=[1 / 6, 2 / 3, 1 / 6])
+    codes, amax = oracle.project_quantize_ternary(X, P3)
+    # sums and differences, written out in float64 (exact for these few terms up to fp32 rounding of each sum)
+    Y = np.zeros((rows, k), dtype=np.float32)
+    for c in range(d):
+        for j in range(k):
+            if P3[c, j] > 0:
+                Y[:, j] = Y[:, j] + X[:, c]
+            elif P3[c, j] < 0:
+                Y[:, j] = Y[:, j] - X[:, c]
+    assert amax == np.float32(np.abs(Y).max())
+    want = np.clip(np.rint(Y * (np.float32(127) / np.float32(amax))), -127, 127).astype(np.int8)
+    assert np.array_equal(codes, want)
+    # the same codes as the dense projection with the signs as its matrix, at every precision
+    for bits in (8, 4, 2):
+        a, am = oracle.project_quantize_ternary(X, P3, bits)
+        b, bm = oracle.project_quantize(X, P3.astype(np.float32), bits)
+        assert np.array_equal(a, b) and am == bm
+    # a column with a single +1 copies an input column; a single -1 negates it; an empty column gives zeros
+    P1 = np.zeros((d, 3), dtype=np.int8)
+    P1[4, 0], P1[7, 1] = 1, -1
+    Xi = rng.integers(-127, 128, (rows, d)).astype(np.float32)
+    Xi[0, 4] = 127.0
+    c1, a1 = oracle.project_quantize_ternary(Xi, P1)
+    assert a1 == 127.0 and np.array_equal(c1[:, 0], Xi[:, 4].astype(np.int8))
+    assert np.array_equal(c1[:, 1], np.clip(-Xi[:, 7], -127, 127).astype(np.int8)) and (c1[:, 2] == 0).all()
+    with pytest.raises(ValueError):
+        oracle.project_quantize_ternary(X, np.full((d, k), 2, dtype=np.int8))
