@@ -160,6 +160,14 @@ dsa_status dsa_project_quantize(const dsa_shape *shape, const void *X, const flo
  *     dsa_predict_workspace_bytes_bits(). */
 dsa_status dsa_project_quantize_bits(const dsa_shape *shape, int32_t bits, const void *X, const float *R,
                                      void *Xt, float *amax_out, void *ws, size_t ws_bytes, void *stream);
+/*   dsa_project_quantize_ternary: the same step with the paper's own projection (equation 5): a sparse random
+ *     matrix P in sqrt(3/k) * {-1, 0, 1}^(d x k), so that Y = X P takes additions and subtractions only.  P3
+ *     (int8 [d,k], row-major, device) holds the signs -1, 0, 1 (other values: undefined codes); the positive
+ *     constant sqrt(3/k) cancels in the quantiser's scale qmax / max|Y| and is left out.  The sums are taken in
+ *     fp32 in increasing c, so the codes equal those of dsa_project_quantize_bits with R = the signs as floats,
+ *     bit for bit.  X, Xt, bits, amax_out, ws as in dsa_project_quantize_bits. */
+dsa_status dsa_project_quantize_ternary(const dsa_shape *shape, int32_t bits, const void *X, const int8_t *P3,
+                                        void *Xt, float *amax_out, void *ws, size_t ws_bytes, void *stream);
 size_t dsa_predict_workspace_bytes_bits(const dsa_shape *shape, int32_t bits);
 dsa_status dsa_predict_mask_bits(const dsa_shape *shape, int32_t bits, const void *Qt, const void *Kt,
                                  int32_t *idx, void *ws, size_t ws_bytes, void *stream);

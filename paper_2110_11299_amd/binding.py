@@ -22,7 +22,7 @@ EXPORTS = [
     "dsa_noalloc_max_mask_bytes", "dsa_approx_rowmax", "dsa_mfma_i8_sustained", "dsa_gather_roof",
     "dsa_threshold_workspace_bytes", "dsa_predict_mask_threshold", "dsa_masked_attention_csr",
     "dsa_project_quantize", "dsa_project_workspace_bytes",
-    "dsa_project_quantize_bits", "dsa_predict_workspace_bytes_bits", "dsa_predict_mask_bits",
+    "dsa_project_quantize_bits", "dsa_project_quantize_ternary", "dsa_predict_workspace_bytes_bits", "dsa_predict_mask_bits",
     "dsa_workspace_bytes_bits", "dsa_attention_fwd_bits",
     "dsa_status_string", "dsa_version",
 ]
@@ -82,6 +82,8 @@ def lib():
         L.dsa_project_quantize.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
         L.dsa_project_quantize_bits.restype = i32
         L.dsa_project_quantize_bits.argtypes = [shp, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.dsa_project_quantize_ternary.restype = i32
+        L.dsa_project_quantize_ternary.argtypes = [shp, i32, vp, vp, vp, vp, vp, sz, vp]
         L.dsa_predict_workspace_bytes_bits.restype = sz
         L.dsa_predict_workspace_bytes_bits.argtypes = [shp, i32]
         L.dsa_predict_mask_bits.restype = i32
@@ -357,6 +359,21 @@ def dsa_project_quantize_bits(shape, bits, X, R, Xt=None, ws=None, want_amax=Tru
     amax = torch.empty(1, dtype=torch.float32, device=X.device) if want_amax else None
     _check(lib().dsa_project_quantize_bits(ctypes.byref(shape), bits, _ptr(X), _ptr(R), _ptr(Xt), _ptr(amax),
                                            _ptr(ws), ws.numel(), _stream()), "dsa_project_quantize_bits")
+    return Xt, amax
+
+
+def dsa_project_quantize_ternary(shape, bits, X, P3, Xt=None, ws=None, want_amax=True):
+    """Projection with a ternary matrix P3 (int8 [d,k] in {-1,0,1}).  Returns (packed codes uint8, amax or None)."""
+    import torch
+    tq, _, _, _ = _dims(shape)
+    tp = _packed_dims(shape, bits)
+    _dev(X, _qkv_dtype(shape), tq); _dev(P3, torch.int8, (shape.d, shape.k))
+    Xt = torch.empty(tp, dtype=torch.uint8, device=X.device) if Xt is None else _dev(Xt, torch.uint8, tp)
+    need = project_workspace_bytes(shape)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=X.device) if ws is None else ws
+    amax = torch.empty(1, dtype=torch.float32, device=X.device) if want_amax else None
+    _check(lib().dsa_project_quantize_ternary(ctypes.byref(shape), bits, _ptr(X), _ptr(P3), _ptr(Xt), _ptr(amax),
+                                              _ptr(ws), ws.numel(), _stream()), "dsa_project_quantize_ternary")
     return Xt, amax
 
 

@@ -35,6 +35,16 @@ def _obj(src: Path) -> Path:
     return OBJDIR / (src.stem + ".o")
 
 
+def _deps(src: Path):
+    """What the object of src was built from, by the compiler's own dependency file (every header
+    the first time)."""
+    dep = _obj(src).with_suffix(".d")
+    if not dep.exists():
+        return [src] + headers()
+    words = dep.read_text().replace("\\\n", " ").split()
+    return [src] + [Path(w) for w in words[1:] if w.endswith(".h") and Path(w).exists() and "/opt/rocm" not in w]
+
+
 def _stale(target: Path, deps) -> bool:
     if not target.exists():
         return True
@@ -49,7 +59,7 @@ def is_stale() -> bool:
 def _compile(hipcc: str, src: Path, verbose: bool) -> None:
     obj = _obj(src)
     tmp = obj.with_suffix(f".tmp{os.getpid()}.o")
-    cmd = [hipcc, *HIPCC_FLAGS, f"-I{INCLUDE}", f"-I{CSRC}", "-c", str(src), "-o", str(tmp)]
+    cmd = [hipcc, *HIPCC_FLAGS, f"-I{INCLUDE}", f"-I{CSRC}", "-MD", "-MF", str(obj.with_suffix(".d")), "-c", str(src), "-o", str(tmp)]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -66,7 +76,7 @@ def build_hip(force: bool = True, verbose: bool = False) -> Path:
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     OBJDIR.mkdir(exist_ok=True)
-    todo = [s for s in sources() if force or _stale(_obj(s), [s] + headers())]
+    todo = [s for s in sources() if force or _stale(_obj(s), _deps(s))]
     jobs = max(1, min(len(todo), int(os.environ.get("MAX_JOBS", "8")), os.cpu_count() or 1))
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         list(pool.map(lambda s: _compile(hipcc, s, verbose), todo))

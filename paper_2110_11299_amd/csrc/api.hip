@@ -1,6 +1,11 @@
 // C ABI of libdsa_hip.so: argument checking on the host, then dispatch to the launchers.
 // Nothing here touches the device before every check has passed.
 #include "dsa_internal.h"
+#include "attention_api.h"
+#include "predict_api.h"
+#include "predict_stream_api.h"
+#include "project_api.h"
+#include "threshold_api.h"
 
 #include <math.h>
 
@@ -217,7 +222,21 @@ dsa_status dsa_project_quantize_bits(const dsa_shape *sh, int32_t bits, const vo
         (reinterpret_cast<uintptr_t>(amax_out) & 3u))
         return DSA_ERR_ALIGN;
     if (ws_bytes < round_up_256(dsa::project_workspace_bytes(*sh))) return DSA_ERR_WORKSPACE;
-    return from_hip(dsa::launch_project_quantize(*sh, bits, X, R, Xt, amax_out, ws, (hipStream_t)stream));
+    return from_hip(dsa::launch_project_quantize(*sh, bits, X, R, nullptr, Xt, amax_out, ws, (hipStream_t)stream));
+}
+
+dsa_status dsa_project_quantize_ternary(const dsa_shape *sh, int32_t bits, const void *X, const int8_t *P3, void *Xt,
+                                        float *amax_out, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!sh || !X || !P3 || !Xt || !ws) return DSA_ERR_NULL;
+    if (bits != 8 && bits != 4 && bits != 2) return DSA_ERR_UNSUPPORTED;
+    if (dsa_status s = check_predict(sh)) return s;
+    if (dsa_status s = check_attention(sh)) return s;
+    if (!aligned16(X) || !aligned16(P3) || !aligned16(Xt) || !aligned16(ws) ||
+        (reinterpret_cast<uintptr_t>(amax_out) & 3u))
+        return DSA_ERR_ALIGN;
+    if (ws_bytes < round_up_256(dsa::project_workspace_bytes(*sh))) return DSA_ERR_WORKSPACE;
+    return from_hip(dsa::launch_project_quantize(*sh, bits, X, nullptr, P3, Xt, amax_out, ws, (hipStream_t)stream));
 }
 
 dsa_status dsa_project_quantize(const dsa_shape *sh, const void *X, const float *R, int8_t *Xt, float *amax_out,

@@ -9,6 +9,7 @@
 // recomputed from the LDS scores while the value rows stream in.  S and P never reach HBM in
 // the fused mode.
 #include "dsa_internal.h"
+#include "attention_api.h"
 
 namespace dsa {
 namespace {

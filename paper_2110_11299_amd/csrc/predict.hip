@@ -3,6 +3,8 @@
 // (section 5.1), and the per-unit top-k that becomes the mask.  Scores are exact integers, so
 // the selection is exact: larger score first, lower key index among equals, list ascending.
 #include "dsa_internal.h"
+#include "predict_api.h"
+#include "predict_stream_api.h"
 #include "wave_select.h"
 
 namespace dsa {

@@ -29,6 +29,7 @@
 //           order, are placed through running counts into an LDS image of the 16 index rows,
 //           which leaves as one contiguous block.
 #include "dsa_internal.h"
+#include "predict_stream_api.h"
 #include "wave_select.h"
 #include "key_stream.h"
 

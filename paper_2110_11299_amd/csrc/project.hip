@@ -5,16 +5,17 @@
 //   Y[r,j] = fma(X[r,d-1], R[d-1,j], ... fma(X[r,1], R[1,j], fma(X[r,0], R[0,j], 0)))   in fp32
 //   amax   = max |Y|,   s = qmax / amax  (fp32 division),   code = clip(rint(Y * s), -qmax, qmax)
 // with qmax = 127 (int8), 7 (INT4, the paper's default prediction precision, section 3.3) or 1 (INT2).
-// Three launches: clear the maximum, project (Y to scratch, maximum by atomic max on the bit
-// pattern of |Y|, which orders like the value for non-negative floats), quantise.
+// Two launches: the maximum of |Y| (per-workgroup maxima), then projection again + quantiser: Y is
+// never stored.
 #include "dsa_internal.h"
+#include "project_api.h"
+
+#include <algorithm>
 
 namespace dsa {
 namespace {
 
 constexpr int kProjThreads = 256;
-
-__global__ void clear_word(unsigned *w) { *w = 0u; }
 
 // 16 bytes of a row widened to fp32.
 template <typename T> struct Chunk;
@@ -40,72 +41,110 @@ template <> struct Chunk<uint16_t> {
     }
 };
 
-// One thread per (row, four consecutive output columns).  The row is read 16 bytes at a time; the
-// four chains still take their terms in increasing c.
-template <typename T>
-__global__ __launch_bounds__(kProjThreads) void project_rows(const T *__restrict__ X, const float *__restrict__ R,
-                                                             float *__restrict__ Y, unsigned *__restrict__ amax_bits,
-                                                             unsigned rows, int d, int k)
+// One lane per row and 16 output columns; a wavefront covers 64 consecutive rows and one chunk of 16
+// columns.  The projection matrix sits in LDS as floats; all lanes of a wavefront read the same 16
+// floats of it (one broadcast read per four multiply-adds), so neither LDS nor memory limits the
+// pass: it runs at the fused multiply-add rate.  Each of the 16 chains takes its terms in
+// increasing c, which fixes the result bit for bit.  A ternary matrix (entries -1, 0, 1: the sparse
+// random projection of equation 5, up to its positive constant sqrt(3/k), which the quantiser's
+// scale absorbs) becomes the floats -1, 0, 1: fma(x, +-1, y) is the exact sum or difference and
+// fma(x, 0, y) leaves y alone, so the chain is the sequence of additions and subtractions itself.
+// PASS 0: per-workgroup maximum of |Y| to block_max[blockIdx.x].  PASS 1: reduce block_max (the grid
+// of pass 0 is at most kProjMaxBlocks), scale, round to nearest even, clip, pack BITS-wide codes.
+constexpr int kProjCols = 16;
+constexpr int kProjMaxBlocks = 1024;
+
+template <typename T, int PASS, int BITS>
+__global__ __launch_bounds__(kProjThreads) void project_lanes(const T *__restrict__ X, const float *__restrict__ R,
+                                                              const int8_t *__restrict__ P3,
+                                                              float *__restrict__ block_max, int n_block_max,
+                                                              uint8_t *__restrict__ Xt, float *__restrict__ amax_out,
+                                                              unsigned rows, int d, int k, unsigned items)
 {
     constexpr int E = Chunk<T>::N;
-    extern __shared__ float sR[];                  // [d][k]
-    for (int i = threadIdx.x; i < d * k; i += kProjThreads) sR[i] = R[i];
+    extern __shared__ float sR[];                  // [d][k], then one float per wavefront
+    float *red = sR + d * k;
+    for (int i = threadIdx.x; i < d * k; i += kProjThreads) sR[i] = R ? R[i] : (float)P3[i];
+    float amax = 0.f;
+    if (PASS == 1) {
+        float m = 0.f;
+        for (int i = threadIdx.x; i < n_block_max; i += kProjThreads) m = fmaxf(m, block_max[i]);
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
+        if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = m;
+    }
     __syncthreads();
-    const int k4 = k / 4;
-    const unsigned item = blockIdx.x * kProjThreads + threadIdx.x;
-    const unsigned r = item / k4;
-    const int j = (item % k4) * 4;
-    float y0 = 0.f, y1 = 0.f, y2 = 0.f, y3 = 0.f;
-    if (r < rows) {
-        const T *x = X + (size_t)r * d;
+    if (PASS == 1) {
+#pragma unroll
+        for (int w = 0; w < kProjThreads / kWave; ++w) amax = fmaxf(amax, red[w]);
+        if (amax_out && blockIdx.x == 0 && threadIdx.x == 0) *amax_out = amax;
+    }
+    constexpr float kQmax = (float)((1 << (BITS - 1)) - 1);
+    const float scale = amax > 0.f ? __fdiv_rn(kQmax, amax) : 0.f;
+    const int chunks = k / kProjCols;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    float seen = 0.f;
+    // work item = (tile of 64 rows, chunk of 16 columns); a wavefront takes items wave, wave + stride, ...
+    for (unsigned item = blockIdx.x * (kProjThreads / kWave) + wave; item < items;
+         item += gridDim.x * (kProjThreads / kWave)) {
+        const unsigned tile = item / chunks;
+        const int j0 = (int)(item % chunks) * kProjCols;
+        const unsigned r = tile * kWave + lane;
+        const bool live = r < rows;
+        const T *x = X + (size_t)(live ? r : rows - 1) * d;
+        float y[kProjCols];
+#pragma unroll
+        for (int j = 0; j < kProjCols; ++j) y[j] = 0.f;
         for (int c0 = 0; c0 < d; c0 += E) {
             float xv[E];
             Chunk<T>::load(x + c0, xv);
 #pragma unroll
             for (int e = 0; e < E; ++e) {
-                const float4 rc = *reinterpret_cast<const float4 *>(sR + (c0 + e) * k + j);
-                y0 = __fmaf_rn(xv[e], rc.x, y0);
-                y1 = __fmaf_rn(xv[e], rc.y, y1);
-                y2 = __fmaf_rn(xv[e], rc.z, y2);
-                y3 = __fmaf_rn(xv[e], rc.w, y3);
+                const float4 *rc = reinterpret_cast<const float4 *>(sR + (c0 + e) * k + j0);
+#pragma unroll
+                for (int q = 0; q < kProjCols / 4; ++q) {
+                    const float4 w = rc[q];
+                    y[4 * q + 0] = __fmaf_rn(xv[e], w.x, y[4 * q + 0]);
+                    y[4 * q + 1] = __fmaf_rn(xv[e], w.y, y[4 * q + 1]);
+                    y[4 * q + 2] = __fmaf_rn(xv[e], w.z, y[4 * q + 2]);
+                    y[4 * q + 3] = __fmaf_rn(xv[e], w.w, y[4 * q + 3]);
+                }
             }
         }
-        *reinterpret_cast<float4 *>(Y + (size_t)r * k + j) = make_float4(y0, y1, y2, y3);
-    }
-    float m = fmaxf(fmaxf(fabsf(y0), fabsf(y1)), fmaxf(fabsf(y2), fabsf(y3)));
+        if (PASS == 0) {
+            if (live) {
 #pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
-    // the atomic only when it can still raise the maximum: after the first few wavefronts almost
-    // none can, and the one hot address stops being a bottleneck
-    if ((threadIdx.x & (kWave - 1)) == 0 && __float_as_uint(m) > __atomic_load_n(amax_bits, __ATOMIC_RELAXED))
-        atomicMax(amax_bits, __float_as_uint(m));
-}
-
-// Four codes per thread, BITS wide each, stored two's complement with 8/BITS codes per byte (code j
-// of a row in bits [BITS * (j mod 8/BITS), + BITS) of byte j / (8/BITS)): 4, 2 or 1 byte per thread.
-template <int BITS>
-__global__ __launch_bounds__(kProjThreads) void quantize_codes(const float *__restrict__ Y,
-                                                               const unsigned *__restrict__ amax_bits,
-                                                               uint8_t *__restrict__ Xt, float *__restrict__ amax_out,
-                                                               size_t n4)
-{
-    constexpr float kQmax = (float)((1 << (BITS - 1)) - 1);
-    const float amax = __uint_as_float(*amax_bits);
-    if (amax_out && blockIdx.x == 0 && threadIdx.x == 0) *amax_out = amax;
-    const float s = amax > 0.f ? __fdiv_rn(kQmax, amax) : 0.f;
-    const size_t i = (size_t)blockIdx.x * kProjThreads + threadIdx.x;
-    if (i >= n4) return;
-    const float4 y = reinterpret_cast<const float4 *>(Y)[i];
-    const float q[4] = {y.x, y.y, y.z, y.w};
-    unsigned packed = 0;
+                for (int j = 0; j < kProjCols; ++j) seen = fmaxf(seen, fabsf(y[j]));
+            }
+        } else if (live) {
+            unsigned packed[kProjCols * BITS / 32 > 0 ? kProjCols * BITS / 32 : 1];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const float v = fminf(fmaxf(rintf(__fmul_rn(q[e], s)), -kQmax), kQmax);
-        packed |= ((unsigned)(int)v & ((1u << BITS) - 1u)) << (BITS * e);
+            for (int i = 0; i < (int)(sizeof(packed) / sizeof(unsigned)); ++i) packed[i] = 0;
+#pragma unroll
+            for (int j = 0; j < kProjCols; ++j) {
+                const float v = fminf(fmaxf(rintf(__fmul_rn(y[j], scale)), -kQmax), kQmax);
+                packed[j * BITS / 32] |= ((unsigned)(int)v & ((1u << BITS) - 1u)) << ((j * BITS) % 32);
+            }
+            // codes j0 .. j0+15 of row r: 16, 8 or 4 bytes at byte (r * k + j0) * BITS / 8
+            uint8_t *dst = Xt + ((size_t)r * k + j0) * BITS / 8;
+            if (BITS == 8) *reinterpret_cast<uint4 *>(dst) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+            else if (BITS == 4) *reinterpret_cast<uint2 *>(dst) = make_uint2(packed[0], packed[1]);
+            else *reinterpret_cast<unsigned *>(dst) = packed[0];
+        }
     }
-    if (BITS == 8) reinterpret_cast<unsigned *>(Xt)[i] = packed;
-    else if (BITS == 4) reinterpret_cast<uint16_t *>(Xt)[i] = (uint16_t)packed;
-    else Xt[i] = (uint8_t)packed;
+    if (PASS == 0) {
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) seen = fmaxf(seen, __shfl_xor(seen, off, kWave));
+        __syncthreads();
+        if (lane == 0) red[wave] = seen;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float m = 0.f;
+#pragma unroll
+            for (int w = 0; w < kProjThreads / kWave; ++w) m = fmaxf(m, red[w]);
+            block_max[blockIdx.x] = m;
+        }
+    }
 }
 
 // Packed codes back to one int8 per code: a thread expands 4 packed bytes.
@@ -137,36 +176,37 @@ __global__ __launch_bounds__(kProjThreads) void unpack_codes(const unsigned *__r
 
 }  // namespace
 
-size_t project_workspace_bytes(const dsa_shape &sh)
-{
-    return (size_t)sh.B * sh.H * sh.L * sh.k * sizeof(float) + 256;
-}
+size_t project_workspace_bytes(const dsa_shape &) { return kProjMaxBlocks * sizeof(float); }
 
-hipError_t launch_project_quantize(const dsa_shape &sh, int bits, const void *X, const float *R, void *Xt,
-                                   float *amax_out, void *ws, hipStream_t st)
+template <typename T>
+hipError_t launch_project_t(const dsa_shape &sh, int bits, const T *X, const float *R, const int8_t *P3, void *Xt,
+                            float *amax_out, void *ws, hipStream_t st)
 {
     const unsigned rows = (unsigned)sh.B * sh.H * sh.L;
-    const size_t n = (size_t)rows * sh.k;
-    float *Y = static_cast<float *>(ws);
-    unsigned *amax_bits = reinterpret_cast<unsigned *>(static_cast<char *>(ws) + n * sizeof(float));
-    hipLaunchKernelGGL(clear_word, dim3(1), dim3(1), 0, st, amax_bits);
-    const size_t items = n / 4;
-    const dim3 grid((unsigned)((items + kProjThreads - 1) / kProjThreads)), block(kProjThreads);
-    const size_t lds = (size_t)sh.d * sh.k * sizeof(float);
-    const void *kern = sh.dtype == DSA_F32 ? reinterpret_cast<const void *>(project_rows<float>)
-                                           : reinterpret_cast<const void *>(project_rows<uint16_t>);
-    if (hipError_t e = allow_dynamic_lds(kern, lds)) return e;
-    if (sh.dtype == DSA_F32)
-        hipLaunchKernelGGL(project_rows<float>, grid, block, lds, st, static_cast<const float *>(X), R, Y, amax_bits,
-                           rows, sh.d, sh.k);
-    else
-        hipLaunchKernelGGL(project_rows<uint16_t>, grid, block, lds, st, static_cast<const uint16_t *>(X), R, Y,
-                           amax_bits, rows, sh.d, sh.k);
+    const unsigned items = ((rows + kWave - 1) / kWave) * (unsigned)(sh.k / kProjCols);
+    const unsigned per_block = kProjThreads / kWave;
+    const unsigned grid = std::min<unsigned>((items + per_block - 1) / per_block, kProjMaxBlocks);
+    const size_t lds = ((size_t)sh.d * sh.k + kProjThreads / kWave) * sizeof(float);
+    float *block_max = static_cast<float *>(ws);
     uint8_t *out = static_cast<uint8_t *>(Xt);
-    if (bits == 8) hipLaunchKernelGGL(quantize_codes<8>, grid, block, 0, st, Y, amax_bits, out, amax_out, items);
-    else if (bits == 4) hipLaunchKernelGGL(quantize_codes<4>, grid, block, 0, st, Y, amax_bits, out, amax_out, items);
-    else hipLaunchKernelGGL(quantize_codes<2>, grid, block, 0, st, Y, amax_bits, out, amax_out, items);
-    return hipGetLastError();
+    auto go = [&](auto kern) -> hipError_t {
+        if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kProjThreads), lds, st, X, R, P3, block_max, (int)grid, out, amax_out,
+                           rows, sh.d, sh.k, items);
+        return hipGetLastError();
+    };
+    if (hipError_t e = go(project_lanes<T, 0, 8>)) return e;
+    if (bits == 8) return go(project_lanes<T, 1, 8>);
+    if (bits == 4) return go(project_lanes<T, 1, 4>);
+    return go(project_lanes<T, 1, 2>);
+}
+
+hipError_t launch_project_quantize(const dsa_shape &sh, int bits, const void *X, const float *R, const int8_t *P3,
+                                   void *Xt, float *amax_out, void *ws, hipStream_t st)
+{
+    if (sh.dtype == DSA_F32)
+        return launch_project_t<float>(sh, bits, static_cast<const float *>(X), R, P3, Xt, amax_out, ws, st);
+    return launch_project_t<uint16_t>(sh, bits, static_cast<const uint16_t *>(X), R, P3, Xt, amax_out, ws, st);
 }
 
 hipError_t launch_unpack_codes(int bits, const void *packed, int8_t *codes, size_t n_codes, hipStream_t st)

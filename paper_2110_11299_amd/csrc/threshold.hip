@@ -11,6 +11,7 @@
 //   fill    one wavefront per unit turns its bitmap into keys at row_ptr[u]; a unit without a key
 //           finds its best key with packed dot products.
 #include "dsa_internal.h"
+#include "threshold_api.h"
 #include "key_stream.h"
 
 namespace dsa {

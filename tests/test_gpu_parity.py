@@ -321,7 +321,7 @@ def test_projection_and_quantiser(dsa, oracle, workload, name):
 
 def test_projection_ragged_and_zero(dsa, oracle):
     import torch
-    for (L, d, k, dtype) in [(1, 64, 16, "f32"), (77, 128, 48, "bf16"), (300, 64, 128, "f32")]:
+    for (L, d, k, dtype) in [(1, 64, 16, "f32"), (77, 128, 48, "bf16"), (300, 64, 128, "f32"), (520, 128, 128, "bf16")]:
         cfg = di.custom_config(B=1, H=3, L=L, d=d, dtype=dtype, rank=3, k=k, keep=1, seed=L)
         x = di.make_inputs(cfg)
         sh = shape_of(dsa, cfg)
@@ -333,6 +333,28 @@ def test_projection_ragged_and_zero(dsa, oracle):
     codes, amax = dsa.dsa_project_quantize(sh, torch.zeros((1, 1, 32, 64), device="cuda"),
                                            torch.ones((64, 16), device="cuda"))
     assert float(amax.item()) == 0.0 and not bool(codes.any())
+
+
+@pytest.mark.parametrize("name,bits", [("C1", 8), ("C2", 8), ("C4f", 8), ("C4f", 4), ("C5", 8), ("C5", 2)])
+def test_ternary_projection(dsa, oracle, workload, name, bits):
+    """Equation 5's sparse random projection (signs -1, 0, 1 with probabilities 1/6, 2/3, 1/6): codes bit-exact
+    against the oracle's additions and subtractions, and equal to the dense projection with the same signs."""
+    import torch
+    x = workload(name)
+    cfg, dev = x.cfg, to_dev(x)
+    sh = shape_of(dsa, cfg)
+    rng = np.random.Generator(np.random.Philox(900 + cfg.seed))
+    P3 = rng.choice(np.array([-1, 0, 1], dtype=np.int8), size=(cfg.d, cfg.k), p=[1 / 6, 2 / 3, 1 / 6])
+    Pd = torch.from_numpy(P3).cuda()
+    print(f"[ternary] {name} bits={bits}", flush=True)
+    for which in ("Q", "K"):
+        packed, amax = dsa.dsa_project_quantize_ternary(sh, bits, dev[which], Pd)
+        dense, amax2 = dsa.dsa_project_quantize_bits(sh, bits, dev[which], Pd.float())
+        torch.cuda.synchronize()
+        want, want_amax = oracle.project_quantize_ternary(getattr(x, which), P3, bits)
+        assert float(amax.item()) == float(want_amax) == float(amax2.item())
+        assert np.array_equal(packed.cpu().numpy().reshape(-1), oracle.pack_codes(want, bits).reshape(-1)), which
+        assert torch.equal(packed, dense)
 
 
 @pytest.mark.parametrize("bits", [4, 2])
