@@ -11,6 +11,7 @@
 #include "project_api.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace dsa {
 namespace {
@@ -54,7 +55,7 @@ template <> struct Chunk<uint16_t> {
 constexpr int kProjCols = 16;
 constexpr int kProjMaxBlocks = 1024;
 
-template <typename T, int PASS, int BITS>
+template <typename T, int PASS, int BITS, bool TERNARY>
 __global__ __launch_bounds__(kProjThreads) void project_lanes(const T *__restrict__ X, const float *__restrict__ R,
                                                               const int8_t *__restrict__ P3,
                                                               float *__restrict__ block_max, int n_block_max,
@@ -64,7 +65,10 @@ __global__ __launch_bounds__(kProjThreads) void project_lanes(const T *__restric
     constexpr int E = Chunk<T>::N;
     extern __shared__ float sR[];                  // [d][k], then one float per wavefront
     float *red = sR + d * k;
-    for (int i = threadIdx.x; i < d * k; i += kProjThreads) sR[i] = R ? R[i] : (float)P3[i];
+    // a dense matrix is read straight from memory through the scalar cache (the address is the same for
+    // all lanes); only the ternary one is widened to floats in LDS
+    if (TERNARY)
+        for (int i = threadIdx.x; i < d * k; i += kProjThreads) sR[i] = (float)P3[i];
     float amax = 0.f;
     if (PASS == 1) {
         float m = 0.f;
@@ -82,7 +86,7 @@ __global__ __launch_bounds__(kProjThreads) void project_lanes(const T *__restric
     constexpr float kQmax = (float)((1 << (BITS - 1)) - 1);
     const float scale = amax > 0.f ? __fdiv_rn(kQmax, amax) : 0.f;
     const int chunks = k / kProjCols;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     float seen = 0.f;
     // work item = (tile of 64 rows, chunk of 16 columns); a wavefront takes items wave, wave + stride, ...
     for (unsigned item = blockIdx.x * (kProjThreads / kWave) + wave; item < items;
@@ -100,14 +104,14 @@ __global__ __launch_bounds__(kProjThreads) void project_lanes(const T *__restric
             Chunk<T>::load(x + c0, xv);
 #pragma unroll
             for (int e = 0; e < E; ++e) {
-                const float4 *rc = reinterpret_cast<const float4 *>(sR + (c0 + e) * k + j0);
+                if (TERNARY) {
+                    const float *rc = sR + (c0 + e) * k + j0;
 #pragma unroll
-                for (int q = 0; q < kProjCols / 4; ++q) {
-                    const float4 w = rc[q];
-                    y[4 * q + 0] = __fmaf_rn(xv[e], w.x, y[4 * q + 0]);
-                    y[4 * q + 1] = __fmaf_rn(xv[e], w.y, y[4 * q + 1]);
-                    y[4 * q + 2] = __fmaf_rn(xv[e], w.z, y[4 * q + 2]);
-                    y[4 * q + 3] = __fmaf_rn(xv[e], w.w, y[4 * q + 3]);
+                    for (int j = 0; j < kProjCols; ++j) y[j] = __fmaf_rn(xv[e], rc[j], y[j]);
+                } else {
+                    const float *rc = R + (c0 + e) * k + j0;     // wavefront-uniform: scalar loads
+#pragma unroll
+                    for (int j = 0; j < kProjCols; ++j) y[j] = __fmaf_rn(xv[e], rc[j], y[j]);
                 }
             }
         }
@@ -195,10 +199,14 @@ hipError_t launch_project_t(const dsa_shape &sh, int bits, const T *X, const flo
                            rows, sh.d, sh.k, items);
         return hipGetLastError();
     };
-    if (hipError_t e = go(project_lanes<T, 0, 8>)) return e;
-    if (bits == 8) return go(project_lanes<T, 1, 8>);
-    if (bits == 4) return go(project_lanes<T, 1, 4>);
-    return go(project_lanes<T, 1, 2>);
+    auto both = [&](auto ternary_tag) -> hipError_t {
+        constexpr bool TERNARY = decltype(ternary_tag)::value;
+        if (hipError_t e = go(project_lanes<T, 0, 8, TERNARY>)) return e;
+        if (bits == 8) return go(project_lanes<T, 1, 8, TERNARY>);
+        if (bits == 4) return go(project_lanes<T, 1, 4, TERNARY>);
+        return go(project_lanes<T, 1, 2, TERNARY>);
+    };
+    return P3 ? both(std::true_type{}) : both(std::false_type{});
 }
 
 hipError_t launch_project_quantize(const dsa_shape &sh, int bits, const void *X, const float *R, const int8_t *P3,
