@@ -19,6 +19,12 @@ _LIB = _HERE / "libdsa_oracle.so"
 _lib = None
 
 CFLAGS = ["-O3", "-march=native", "-fopenmp", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra"]
+# DSA_ORACLE_SANITIZE=1 builds a second library with AddressSanitizer and UndefinedBehaviorSanitizer and
+# loads that one (the process then needs libasan preloaded: see the sanitizer command in the design doc).
+if os.environ.get("DSA_ORACLE_SANITIZE") == "1":
+    CFLAGS = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+              "-fopenmp", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra"]
+    _LIB = _HERE / "libdsa_oracle_san.so"
 
 
 def build(force: bool = False) -> Path:
