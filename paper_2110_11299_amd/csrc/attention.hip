@@ -380,11 +380,12 @@ constexpr int kGroupWaves = 4;
 // (The launch bound is twice the launched size: with at most 256 registers per lane the compiler
 // gives the matrix core plain VGPR destinations instead of accumulation registers that every
 // other instruction would have to copy from.)
-template <int D>
+// MODE kFused: Q,K,V,idx -> O.  kSddmm: Q,K,idx -> S (scaled scores of the 8 rows).  kSpmm: Pin,V,idx -> O.
+template <int D, int MODE>
 __global__ __launch_bounds__(2 * kGroupWaves *kWave) void attention_groups_bf16(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
-    const int32_t *__restrict__ idx, float *__restrict__ O, int L, int keep, int keep_pad, float scale,
-    unsigned total_groups)
+    const int32_t *__restrict__ idx, const float *__restrict__ Pin, float *__restrict__ S, float *__restrict__ O,
+    int L, int keep, int keep_pad, float scale, unsigned total_groups)
 {
     constexpr int KS = D / 32;             // contraction steps of Q K^T
     constexpr int CT = D / 16;             // 16-column tiles of the output
@@ -410,7 +411,7 @@ __global__ __launch_bounds__(2 * kGroupWaves *kWave) void attention_groups_bf16(
     bf16x8 qop[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-        const uint4 raw = c < 8 ? *reinterpret_cast<const uint4 *>(Q + ((size_t)n * L + u * 8 + c) * D + 32 * s + 8 * g)
+        const uint4 raw = (MODE != kSpmm && c < 8) ? *reinterpret_cast<const uint4 *>(Q + ((size_t)n * L + u * 8 + c) * D + 32 * s + 8 * g)
                                 : make_uint4(0, 0, 0, 0);
         qop[s] = __builtin_bit_cast(bf16x8, raw);
     }
@@ -424,6 +425,7 @@ __global__ __launch_bounds__(2 * kGroupWaves *kWave) void attention_groups_bf16(
     // kept in flight: the rows of tile t + PF are requested as soon as tile t has been consumed.
     float mx = -INFINITY;
     constexpr int PF = 1;          // deeper rings measured no faster
+    if (MODE != kSpmm) {
     bf16x8 kring[PF][KS];
 #pragma unroll
     for (int p = 0; p < PF; ++p) {
@@ -452,6 +454,27 @@ __global__ __launch_bounds__(2 * kGroupWaves *kWave) void attention_groups_bf16(
                 }
                 if (c < 8) *reinterpret_cast<v4f *>(sS + c * keep_pad + tile + 4 * g) = acc;
             }
+        }
+    }
+    }
+    if (MODE == kSddmm) {
+        // the 8 rows of scores leave through LDS: consecutive lanes write consecutive entries of a row
+        wave_lds_fence();
+        if (live) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                float *dst = S + ((size_t)n * L + u * 8 + r) * keep;
+                for (int t = lane; t < keep; t += kWave) dst[t] = sS[r * keep_pad + t];
+            }
+        }
+        return;
+    }
+    if (MODE == kSpmm) {
+        // the given weights come in the same way (0 beyond the list)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const float *src = Pin + ((size_t)n * L + u * 8 + r) * keep;
+            for (int t = lane; t < keep_pad; t += kWave) sS[r * keep_pad + t] = t < keep ? src[t] : 0.f;
         }
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
@@ -494,7 +517,8 @@ __global__ __launch_bounds__(2 * kGroupWaves *kWave) void attention_groups_bf16(
                 bf16x8 pa;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float p0 = __expf(s0[i] - mx), p1 = __expf(s1[i] - mx);
+                    const float p0 = MODE == kSpmm ? s0[i] : __expf(s0[i] - mx);
+                    const float p1 = MODE == kSpmm ? s1[i] : __expf(s1[i] - mx);
                     z += p0 + p1;
                     pa[i] = (__bf16)p0;
                     pa[4 + i] = (__bf16)p1;
@@ -521,7 +545,7 @@ __global__ __launch_bounds__(2 * kGroupWaves *kWave) void attention_groups_bf16(
     if (live) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const float inv = 1.f / __shfl(z, (4 * g + i) & 7, kWave);
+            const float inv = MODE == kSpmm ? 1.f : 1.f / __shfl(z, (4 * g + i) & 7, kWave);
             if (g < 2) {
                 float *out = O + ((size_t)n * L + u * 8 + 4 * g + i) * D + c;
 #pragma unroll
@@ -585,19 +609,28 @@ size_t groups_lds_bytes(const dsa_shape &sh)
     return kGroupWaves * (9 * keep_pad * sizeof(float) + 32 * ((size_t)sh.d * 2 + 16));
 }
 
-template <int D>
+template <int D, int MODE>
 hipError_t launch_groups(const dsa_shape &sh, const void *Q, const void *K, const void *V, const int32_t *idx,
-                         float *O, hipStream_t st)
+                         const float *Pin, float *S, float *O, hipStream_t st)
 {
     const unsigned groups = (unsigned)sh.B * sh.H * (sh.L / 8);
     const int keep_pad = (sh.keep + 31) / 32 * 32;
     const size_t lds = groups_lds_bytes(sh);
-    auto kern = attention_groups_bf16<D>;
+    auto kern = attention_groups_bf16<D, MODE>;
     if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
     hipLaunchKernelGGL(kern, dim3((groups + kGroupWaves - 1) / kGroupWaves), dim3(kGroupWaves * kWave), lds, st,
                        static_cast<const uint16_t *>(Q), static_cast<const uint16_t *>(K),
-                       static_cast<const uint16_t *>(V), idx, O, sh.L, sh.keep, keep_pad, sh.scale, groups);
+                       static_cast<const uint16_t *>(V), idx, Pin, S, O, sh.L, sh.keep, keep_pad, sh.scale, groups);
     return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_groups_d(AttnMode mode, const dsa_shape &sh, const void *Q, const void *K, const void *V,
+                           const int32_t *idx, const float *Pin, float *S, float *O, hipStream_t st)
+{
+    if (mode == kSddmm) return launch_groups<D, kSddmm>(sh, Q, K, V, idx, Pin, S, O, st);
+    if (mode == kSpmm) return launch_groups<D, kSpmm>(sh, Q, K, V, idx, Pin, S, O, st);
+    return launch_groups<D, kFused>(sh, Q, K, V, idx, Pin, S, O, st);
 }
 
 }  // namespace
@@ -615,9 +648,9 @@ hipError_t launch_attention(AttnMode mode, const dsa_shape &sh, const void *Q, c
         if (sh.d == 64) return launch_rows<float, 64>(mode, sh, Q, K, V, idx, Pin, S, O, st);
         return launch_rows<float, 128>(mode, sh, Q, K, V, idx, Pin, S, O, st);
     }
-    if (mode == kFused && sh.vec == 8 && groups_lds_bytes(sh) <= 144 * 1024) {
-        if (sh.d == 64) return launch_groups<64>(sh, Q, K, V, idx, O, st);
-        return launch_groups<128>(sh, Q, K, V, idx, O, st);
+    if (sh.vec == 8 && groups_lds_bytes(sh) <= 144 * 1024) {
+        if (sh.d == 64) return launch_groups_d<64>(mode, sh, Q, K, V, idx, Pin, S, O, st);
+        return launch_groups_d<128>(mode, sh, Q, K, V, idx, Pin, S, O, st);
     }
     if (sh.d == 64) return launch_rows<uint16_t, 64>(mode, sh, Q, K, V, idx, Pin, S, O, st);
     return launch_rows<uint16_t, 128>(mode, sh, Q, K, V, idx, Pin, S, O, st);
