@@ -66,8 +66,8 @@ __device__ __forceinline__ int unit_max(int x)
 // One group of 8 tiles of pass 1 (t8, the group's first tile, is a multiple of 8).  SAFE: the group may
 // touch keys beyond L or tiles beyond the quarter: requests are clamped to the last key row and such
 // scores become INT32_MIN.
-template <bool SAFE, int K, int NB>
-__device__ __forceinline__ void pass1_group(int (&bmax)[NB], KeyStream<K> &ks, int t8, int b0, int key_lo, int key_lim)
+template <bool SAFE, int K, int VEC, int NB>
+__device__ __forceinline__ void pass1_group(int (&bmax)[NB], KeyStream<K, VEC> &ks, int t8, int b0, int key_lo, int key_lim)
 {
     const unsigned next = ks.next_of(t8);
 #pragma unroll
@@ -96,7 +96,7 @@ __device__ __forceinline__ int unit_excl_scan(int x, int g, int *total)
 
 // K is the projection dimension k (a template argument, so that the byte offsets of the key stream
 // are constants).
-template <int K, int NB>
+template <int K, int VEC, int NB>
 __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const int8_t *__restrict__ Qt,
                                                            const int8_t *__restrict__ Kt,
                                                            int32_t *__restrict__ idx, int L, int keep,
@@ -119,7 +119,8 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
     const unsigned task = task_live ? slot : total_tasks - 1;
     const unsigned n = task / (unsigned)tasks_per_head;
     const int u0 = (int)(task % (unsigned)tasks_per_head) * kStreamUnits;
-    const int nu = min(kStreamUnits, L - u0);    // real units of this wavefront
+    const int G = L / VEC;                       // units of a head (rows, or groups of VEC rows)
+    const int nu = min(kStreamUnits, G - u0);    // real units of this wavefront
     const int Lq = stream_quarter(L);
     const int NT = Lq / 4;                       // tiles of 4 keys per quarter: a multiple of 8
     const int NWL = Lq / 32;                     // bitmap words per lane
@@ -131,7 +132,8 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
 
     const int8_t *Kh = Kt + (size_t)n * L * k;
     const int8_t *Qh = Qt + (size_t)n * L * k;
-    const bool unit_live = u0 + c < L;
+    const bool unit_live = u0 + c < G;
+    const int8_t *Qunit = Qh + (size_t)min(u0 + c, G - 1) * (VEC * k);     // the unit's VEC rows are contiguous
 
     // tiles [0, tfull) hold only real keys in all four quarters
     int tfull = NT;
@@ -140,8 +142,8 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
     const int key_lo = g * Lq;                   // first key of this lane's quarter
     const int key_lim = min(L, key_lo + Lq);     // its keys are below key_lim
 
-    KeyStream<K> ks;
-    ks.start(Kh, Qh + (size_t)min(u0 + c, L - 1) * k, unit_live, lane, Lq, L);
+    KeyStream<K, VEC> ks;
+    ks.start(Kh, Qunit, unit_live, lane, Lq, L);
 
     // ---- pass 1: bucket maxima -----------------------------------------------------------------
     int bmax[NB];
@@ -155,9 +157,9 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
                 if (t8 < NT) {
                     // a group is plain when it and every request it makes stay inside the full tiles
                     if (t8 + 8 + 2 + PF <= tfull)
-                        pass1_group<false, K, NB>(bmax, ks, t8, b0, key_lo, key_lim);
+                        pass1_group<false, K, VEC, NB>(bmax, ks, t8, b0, key_lo, key_lim);
                     else
-                        pass1_group<true, K, NB>(bmax, ks, t8, b0, key_lo, key_lim);
+                        pass1_group<true, K, VEC, NB>(bmax, ks, t8, b0, key_lo, key_lim);
                 }
             }
         }
@@ -174,7 +176,7 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
         }
         // an empty bucket holds INT32_MIN: start below every possible score instead (the host only
         // takes this kernel when at least keep buckets of a unit hold a key)
-        lo = max(unit_min(lo), -(k * 127 * 127) - 1);
+        lo = max(unit_min(lo), -(VEC * k * 128 * 128) - 1);
         hi = max(unit_max(hi), lo);
         // Invariant: count(maxima >= lo) >= keep, count(maxima >= hi + 1) < keep.  A unit is done when
         // lo == hi, or as soon as a probe lands within `slack` of keep.
@@ -196,13 +198,13 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
     // ---- pass 2: bitmap of candidates (score >= T0) ----------------------------------------------
     int mine = 0;                                // candidates in this lane's quarter
     {
-        ks.restart();
+        ks.restart(-T0);
         for (int w = 0; w < NWL; ++w) {
             unsigned word;
             if (8 * w + 8 + 2 + PF <= tfull) {
-                word = pass2_word<false, K>(ks, 8 * w, T0);
+                word = pass2_word<false, K, VEC>(ks, 8 * w);
             } else {
-                word = pass2_word<true, K>(ks, 8 * w, T0);
+                word = pass2_word<true, K, VEC>(ks, 8 * w);
                 const int nv = key_lim - (key_lo + 32 * w);      // real keys in this word
                 word = nv >= 32 ? word : nv <= 0 ? 0u : word & ((1u << nv) - 1u);
             }
@@ -224,15 +226,15 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
     const bool gt_fits = NWL * kWave * (int)sizeof(unsigned) <= kStreamUnits * kStreamStride * (int)sizeof(uint16_t);
     if (gt_fits && __ballot(nc > kStreamCap && unit_live) != 0) {
         const bool over = nc > kStreamCap && unit_live;
-        const int thr = over ? T0 + 1 : INT32_MAX;
+        const int thr = over ? T0 + 1 : kSweepLimit;       // above every score: no bit for the other units
         int above = 0;
-        ks.restart();
+        ks.restart(-thr);
         for (int w = 0; w < NWL; ++w) {
             unsigned word;
             if (8 * w + 8 + 2 + PF <= tfull) {
-                word = pass2_word<false, K>(ks, 8 * w, thr);
+                word = pass2_word<false, K, VEC>(ks, 8 * w);
             } else {
-                word = pass2_word<true, K>(ks, 8 * w, thr);
+                word = pass2_word<true, K, VEC>(ks, 8 * w);
                 const int nv = key_lim - (key_lo + 32 * w);
                 word = nv >= 32 ? word : nv <= 0 ? 0u : word & ((1u << nv) - 1u);
             }
@@ -291,13 +293,13 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
     for (unsigned long long todo = __ballot(!fits && unit_live && g == 0); todo != 0; todo &= todo - 1) {
         const int uu = __ffsll((long long)todo) - 1;             // lane index = unit index for g == 0
         const int lo0 = __builtin_amdgcn_readlane(T0, uu);
-        const int *qu = reinterpret_cast<const int *>(Qh + (size_t)(u0 + uu) * k);
-        int32_t *out = idx + ((size_t)n * L + u0 + uu) * keep;
+        const int *qu = reinterpret_cast<const int *>(Qh + (size_t)(u0 + uu) * (VEC * k));
+        int32_t *out = idx + ((size_t)n * G + u0 + uu) * keep;
         auto flagged_score = [&](int j) -> int {
             if (j >= L) return INT32_MIN;
             const int q = j / Lq, r = j - q * Lq;               // quarter, key inside it
             if (!((bitmap[(r >> 5) * kWave + 16 * q + uu] >> (r & 31)) & 1u)) return INT32_MIN;
-            return unit_key_score(qu, Kh + (size_t)j * k, 1, k / 4);
+            return unit_key_score(qu, Kh + (size_t)j * k, VEC, k / 4);
         };
         int hi = INT32_MIN;
         for (int j = lane; j < L; j += kWave) hi = max(hi, flagged_score(j));
@@ -332,10 +334,20 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
     const int run = active ? (nc + 3) >> 2 : 0;          // candidates per lane, <= kStreamSlots
     const int first = g * run;
     const int run_max = wave_max(run);                   // wavefront-uniform
-    int qrow[K / 4];
+    // The unit's query side as packed int8: its row (VEC = 1), or the sum of its VEC rows in the two
+    // parts of the key stream (the score is linear in the query).
+    int qrow[K / 4], qhi[VEC == 1 ? 1 : K / 4];
 #pragma unroll
-    for (int i = 0; i < K / 4; ++i)
-        qrow[i] = reinterpret_cast<const int *>(Qh + (size_t)min(u0 + c, L - 1) * k)[i];
+    for (int i = 0; i < K / 4; ++i) {
+        if (VEC == 1) {
+            qrow[i] = reinterpret_cast<const int *>(Qunit)[i];
+        } else {
+            int sum[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int r = 0; r < VEC; ++r) add_bytes(sum, reinterpret_cast<const int *>(Qunit + r * K)[i]);
+            split_sums(sum, qrow[i], qhi[i]);
+        }
+    }
     int sc[kStreamSlots];
     int top = INT32_MIN;
 #pragma unroll
@@ -355,14 +367,21 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
             }
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                int s = 0;
+                int s = 0, sh = 0;
 #pragma unroll
                 for (int q4 = 0; q4 < K / 16; ++q4) {
                     s = __builtin_amdgcn_sdot4(qrow[4 * q4 + 0], kk[j][q4].x, s, false);
                     s = __builtin_amdgcn_sdot4(qrow[4 * q4 + 1], kk[j][q4].y, s, false);
                     s = __builtin_amdgcn_sdot4(qrow[4 * q4 + 2], kk[j][q4].z, s, false);
                     s = __builtin_amdgcn_sdot4(qrow[4 * q4 + 3], kk[j][q4].w, s, false);
+                    if (VEC != 1) {
+                        sh = __builtin_amdgcn_sdot4(qhi[4 * q4 + 0], kk[j][q4].x, sh, false);
+                        sh = __builtin_amdgcn_sdot4(qhi[4 * q4 + 1], kk[j][q4].y, sh, false);
+                        sh = __builtin_amdgcn_sdot4(qhi[4 * q4 + 2], kk[j][q4].z, sh, false);
+                        sh = __builtin_amdgcn_sdot4(qhi[4 * q4 + 3], kk[j][q4].w, sh, false);
+                    }
                 }
+                s += 128 * sh;
                 const bool valid = j0 + j < run && first + j0 + j < nc;
                 sc[j0 + j] = valid ? s : INT32_MIN;
                 top = max(top, sc[j0 + j]);
@@ -438,7 +457,7 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
     // the rows of this wavefront's units are contiguous in memory; rows of units that took the slow path
     // were written there and are skipped
     {
-        int32_t *out = idx + ((size_t)n * L + u0) * keep;
+        int32_t *out = idx + ((size_t)n * G + u0) * keep;
         const unsigned fit_units = (unsigned)__ballot(fits && g == 0);      // bit = unit
         for (int uu = 0; uu < nu; ++uu) {
             if (!((fit_units >> uu) & 1u) || !task_live) continue;
@@ -456,14 +475,14 @@ size_t stream_words_per_wave(const dsa_shape &sh)
 }
 size_t stream_lds_bytes(const dsa_shape &sh) { return sizeof(unsigned) * stream_words_per_wave(sh) * kStreamWaves; }
 
-template <int K, int NB>
+template <int K, int VEC, int NB>
 hipError_t launch_stream_t(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *idx, hipStream_t st)
 {
     const size_t words_per_wave = stream_words_per_wave(sh);
     const size_t lds = stream_lds_bytes(sh);
-    auto kern = predict_stream<K, NB>;
+    auto kern = predict_stream<K, VEC, NB>;
     if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
-    const int tasks_per_head = (sh.L + kStreamUnits - 1) / kStreamUnits;
+    const int tasks_per_head = (sh.L / VEC + kStreamUnits - 1) / kStreamUnits;
     const unsigned tasks = (unsigned)sh.B * sh.H * tasks_per_head;
     hipLaunchKernelGGL(kern, dim3((tasks + kStreamWaves - 1) / kStreamWaves), dim3(kStreamWaves * kWave), lds, st, Qt, Kt,
                        idx, sh.L, sh.keep, tasks_per_head, tasks, (int)words_per_wave);
@@ -497,20 +516,29 @@ int stream_nb(int L)
 // (so that about 1.25 * keep candidates survive) and a candidate list that fits the register path.
 bool stream_predict_fits(const dsa_shape &sh)
 {
-    if (sh.vec != 1 || (sh.k != 16 && sh.k != 32 && sh.k != 64) || sh.L > kStreamMaxL) return false;
+    if ((sh.vec != 1 && sh.vec != 4 && sh.vec != 8) || (sh.k != 16 && sh.k != 32 && sh.k != 64)) return false;
+    if (sh.L > kStreamMaxL) return false;
     if (sh.keep > kStreamCap * 5 / 8) return false;     // about 1.25 * keep candidates, with room to spare
     if (4 * stream_buckets(sh.L, stream_nb(sh.L)) < 5 * sh.keep) return false;
     return stream_lds_bytes(sh) <= 160 * 1024;
 }
 
+template <int K, int VEC>
+hipError_t launch_stream_kv(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *idx, hipStream_t st)
+{
+    switch (stream_nb(sh.L)) {
+    case 32: return launch_stream_t<K, VEC, 32>(sh, Qt, Kt, idx, st);
+    case 64: return launch_stream_t<K, VEC, 64>(sh, Qt, Kt, idx, st);
+    default: return launch_stream_t<K, VEC, kStreamLongNB>(sh, Qt, Kt, idx, st);
+    }
+}
+
 template <int K>
 hipError_t launch_stream_k(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *idx, hipStream_t st)
 {
-    switch (stream_nb(sh.L)) {
-    case 32: return launch_stream_t<K, 32>(sh, Qt, Kt, idx, st);
-    case 64: return launch_stream_t<K, 64>(sh, Qt, Kt, idx, st);
-    default: return launch_stream_t<K, kStreamLongNB>(sh, Qt, Kt, idx, st);
-    }
+    if (sh.vec == 1) return launch_stream_kv<K, 1>(sh, Qt, Kt, idx, st);
+    if (sh.vec == 4) return launch_stream_kv<K, 4>(sh, Qt, Kt, idx, st);
+    return launch_stream_kv<K, 8>(sh, Qt, Kt, idx, st);
 }
 
 hipError_t launch_predict_stream(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int32_t *idx,

@@ -43,14 +43,15 @@ __global__ __launch_bounds__(kWave, 4) void threshold_sweep(const int8_t *__rest
 
     KeyStream<K> ks;
     ks.start(Kh, Qh + (size_t)min(u0 + c, L - 1) * K, unit_live, lane, Lq, L);
+    ks.restart(-max(-kSweepLimit, min(theta, kSweepLimit)));     // no score lies beyond the limits
     unsigned *words = bitmap + (size_t)task * NWL * kWave + lane;
     int mine = 0;
     for (int w = 0; w < NWL; ++w) {
         unsigned word;
         if (8 * w + 8 + 2 + PF <= tfull) {
-            word = pass2_word<false, K>(ks, 8 * w, theta);
+            word = pass2_word<false, K, 1>(ks, 8 * w);
         } else {
-            word = pass2_word<true, K>(ks, 8 * w, theta);
+            word = pass2_word<true, K, 1>(ks, 8 * w);
             const int nv = key_lim - (key_lo + 32 * w);      // real keys in this word
             word = nv >= 32 ? word : nv <= 0 ? 0u : word & ((1u << nv) - 1u);
         }
