@@ -34,6 +34,7 @@
 #include "key_stream.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace dsa {
 namespace {
@@ -43,8 +44,16 @@ constexpr int kStreamSlots = 88;        // candidate scores a lane holds in regi
 constexpr int kStreamCap = 4 * kStreamSlots;   // candidates of one unit (its four lanes)
 constexpr int kStreamStride = kStreamCap + 2;  // list entries per unit in LDS: one spare slot, kept even
 constexpr int kStreamMaxL = 8192;       // bitmap of 16 units in LDS: 2 * L bytes per wavefront
-constexpr int kStreamWaves = 1;         // wavefronts (tasks) per workgroup (several share nothing but the launch)
+constexpr int kStreamWaves = kStageWaves;      // wavefronts (tasks) per workgroup: same head, the key sweeps are shared
 constexpr int kStreamLongNB = 128;      // bucket maxima per lane for long sequences
+
+// Words at the start of a wavefront's LDS: the bitmap of its 16 units (word w of lane l at w * 64 + l),
+// later the image of the 16 index rows (one spare slot); a multiple of 16 bytes.
+__host__ __device__ inline int stream_head_words(int L, int keep)
+{
+    const int bitmap = stream_quarter(L) / 32 * kWave, rows = (kStreamUnits * keep + 2) / 2;
+    return ((bitmap > rows ? bitmap : rows) + 3) & ~3;
+}
 
 // Sum / minimum / maximum over the four lanes (c, 0..3) that share a unit; every one of them gets it.
 __device__ __forceinline__ int unit_sum(int x)
@@ -66,10 +75,10 @@ __device__ __forceinline__ int unit_max(int x)
 // One group of 8 tiles of pass 1 (t8, the group's first tile, is a multiple of 8).  SAFE: the group may
 // touch keys beyond L or tiles beyond the quarter: requests are clamped to the last key row and such
 // scores become INT32_MIN.
-template <bool SAFE, int K, int VEC, int NB>
-__device__ __forceinline__ void pass1_group(int (&bmax)[NB], KeyStream<K, VEC> &ks, int t8, int b0, int key_lo, int key_lim)
+template <bool SAFE, int PAR, class Stream, int NB>
+__device__ __forceinline__ void pass1_group(int (&bmax)[NB], Stream &ks, int t8, int b0, int key_lo, int key_lim)
 {
-    const unsigned next = ks.next_of(t8);
+    const unsigned next = ks.template begin_group<PAR>(t8);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         v4i cur = ks.template next_tile<SAFE>(t8, j, next);
@@ -80,6 +89,7 @@ __device__ __forceinline__ void pass1_group(int (&bmax)[NB], KeyStream<K, VEC> &
         bmax[b0 + j] = max(max(bmax[b0 + j], cur[0]), max(max(cur[1], cur[2]), cur[3]));
         __builtin_amdgcn_sched_barrier(0);                           // keep the stream in order
     }
+    ks.end_group();
 }
 
 // Exclusive prefix and total of a per-lane count over the four lanes (c, 0..3) of a unit, in lane
@@ -100,25 +110,25 @@ template <int K, int VEC, int NB>
 __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const int8_t *__restrict__ Qt,
                                                            const int8_t *__restrict__ Kt,
                                                            int32_t *__restrict__ idx, int L, int keep,
-                                                           int tasks_per_head, unsigned total_tasks,
+                                                           int tasks_per_head, int wgs_per_head,
                                                            int lds_words_per_wave)
 {
     constexpr int k = K;
-    constexpr int PF = kStreamPrefetch;
-    static_assert(PF == 8 && NB % 8 == 0, "groups of 8 tiles: one trip of the ring, one bitmap word");
+    static_assert(kStreamPrefetch == 8 && NB % 32 == 0, "groups of 8 tiles: one trip of the ring, one bitmap word; runs of 4 groups");
     extern __shared__ unsigned smem_all[];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 15, g = lane >> 4;
     unsigned *smem = smem_all + wave * lds_words_per_wave;
-    // The wavefronts of a workgroup are independent: each has its own task and its own LDS.  A wavefront
-    // without a task mirrors the last one and writes nothing.
-    const unsigned slot = xcd_contiguous(blockIdx.x, gridDim.x) * kStreamWaves + wave;
-    const bool task_live = slot < total_tasks;
-    const unsigned task = task_live ? slot : total_tasks - 1;
-    const unsigned n = task / (unsigned)tasks_per_head;
-    const int u0 = (int)(task % (unsigned)tasks_per_head) * kStreamUnits;
+    // The wavefronts of a workgroup take consecutive tasks of one head: each has its own units and its
+    // own LDS, the key sweeps they make together.  A wavefront without a task mirrors the head's last
+    // one and writes nothing.
+    const unsigned wg = xcd_contiguous(blockIdx.x, gridDim.x);
+    const unsigned n = wg / (unsigned)wgs_per_head;
+    const int slot = (int)(wg % (unsigned)wgs_per_head) * kStreamWaves + wave;
+    const bool task_live = slot < tasks_per_head;
+    const int u0 = min(slot, tasks_per_head - 1) * kStreamUnits;
     const int G = L / VEC;                       // units of a head (rows, or groups of VEC rows)
     const int nu = min(kStreamUnits, G - u0);    // real units of this wavefront
     const int Lq = stream_quarter(L);
@@ -126,7 +136,7 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
     const int NWL = Lq / 32;                     // bitmap words per lane
     // LDS: [bitmap: word w of lane l at w * 64 + l | later the image of the 16 index rows][lists]
     unsigned *bitmap = smem;
-    const int head_words = max(NWL * kWave, (kStreamUnits * keep + 2) / 2);       // rows: one spare slot
+    const int head_words = stream_head_words(L, keep);
     uint16_t *rows = reinterpret_cast<uint16_t *>(smem);                       // [16][keep]
     uint16_t *list = reinterpret_cast<uint16_t *>(smem + head_words) + c * kStreamStride;   // this unit's list
 
@@ -142,27 +152,43 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
     const int key_lo = g * Lq;                   // first key of this lane's quarter
     const int key_lim = min(L, key_lo + Lq);     // its keys are below key_lim
 
-    KeyStream<K, VEC> ks;
-    ks.start(Kh, Qunit, unit_live, lane, Lq, L);
+    // the four staging buffers of the sweeps lie where the lists of the four wavefronts will be
+    StagedKeyStream<K, VEC> ks;
+    static_assert(StagedKeyStream<K, VEC>::kBufBytes <= kStreamUnits * kStreamStride * sizeof(uint16_t), "a buffer fits a list area");
+    ks.start(Kh, Qunit, unit_live, (int)threadIdx.x, Lq, L, (unsigned)head_words / 4u, (unsigned)lds_words_per_wave / 4u);
 
     // ---- pass 1: bucket maxima -----------------------------------------------------------------
     int bmax[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) bmax[b] = INT32_MIN;
     {
-        for (int t0 = 0; t0 < NT; t0 += NB) {
-#pragma unroll
-            for (int b0 = 0; b0 < NB; b0 += 8) {
-                const int t8 = t0 + b0;
-                if (t8 < NT) {
-                    // a group is plain when it and every request it makes stay inside the full tiles
-                    if (t8 + 8 + 2 + PF <= tfull)
-                        pass1_group<false, K, VEC, NB>(bmax, ks, t8, b0, key_lo, key_lim);
-                    else
-                        pass1_group<true, K, VEC, NB>(bmax, ks, t8, b0, key_lo, key_lim);
-                }
+        // A group is plain when every tile it touches holds only real keys.  Whole rounds of NB tiles that
+        // are plain run without a test per group.
+        constexpr int LA = decltype(ks)::kLookahead;
+        auto group = [&](int t8, int b0, auto par, auto checked) {
+            constexpr int PAR = decltype(par)::value;
+            if (!decltype(checked)::value) {
+                pass1_group<false, PAR>(bmax, ks, t8, b0, key_lo, key_lim);
+            } else if (t8 < NT) {
+                if (t8 + 8 + LA <= tfull)
+                    pass1_group<false, PAR>(bmax, ks, t8, b0, key_lo, key_lim);
+                else
+                    pass1_group<true, PAR>(bmax, ks, t8, b0, key_lo, key_lim);
             }
-        }
+        };
+        auto round = [&](int t0, auto checked) {
+#pragma unroll
+            for (int b0 = 0; b0 < NB; b0 += 32) {
+                group(t0 + b0, b0, std::integral_constant<int, 0>{}, checked);
+                group(t0 + b0 + 8, b0 + 8, std::integral_constant<int, 1>{}, checked);
+                group(t0 + b0 + 16, b0 + 16, std::integral_constant<int, 2>{}, checked);
+                group(t0 + b0 + 24, b0 + 24, std::integral_constant<int, 3>{}, checked);
+            }
+        };
+        int t0 = 0;
+        for (; t0 + NB + LA <= tfull; t0 += NB) round(t0, std::false_type{});
+        for (; t0 < NT; t0 += NB) round(t0, std::true_type{});
+        ks.finish();
     }
 
     // ---- bound: T0 per unit, 16 units at once ---------------------------------------------------
@@ -199,18 +225,34 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
     int mine = 0;                                // candidates in this lane's quarter
     {
         ks.restart(-T0);
-        for (int w = 0; w < NWL; ++w) {
+        constexpr int LA = decltype(ks)::kLookahead;
+        auto sweep_word = [&](int w, auto par, auto checked) {
+            constexpr int PAR = decltype(par)::value;
             unsigned word;
-            if (8 * w + 8 + 2 + PF <= tfull) {
-                word = pass2_word<false, K, VEC>(ks, 8 * w);
+            if (!decltype(checked)::value) {
+                word = pass2_word<false, PAR>(ks, 8 * w);
+            } else if (w >= NWL) {
+                return;
+            } else if (8 * w + 8 + LA <= tfull) {
+                word = pass2_word<false, PAR>(ks, 8 * w);
             } else {
-                word = pass2_word<true, K, VEC>(ks, 8 * w);
+                word = pass2_word<true, PAR>(ks, 8 * w);
                 const int nv = key_lim - (key_lo + 32 * w);      // real keys in this word
                 word = nv >= 32 ? word : nv <= 0 ? 0u : word & ((1u << nv) - 1u);
             }
             bitmap[w * kWave + lane] = word;
             mine += __popc(word);
-        }
+        };
+        auto sweep4 = [&](int w, auto checked) {
+            sweep_word(w, std::integral_constant<int, 0>{}, checked);
+            sweep_word(w + 1, std::integral_constant<int, 1>{}, checked);
+            sweep_word(w + 2, std::integral_constant<int, 2>{}, checked);
+            sweep_word(w + 3, std::integral_constant<int, 3>{}, checked);
+        };
+        int w = 0;
+        for (; 8 * (w + 4) + LA <= tfull; w += 4) sweep4(w, std::false_type{});
+        for (; w < NWL; w += 4) sweep4(w, std::true_type{});
+        ks.finish();
     }
 
     // ---- ties: units whose candidates do not fit ---------------------------------------------------
@@ -228,13 +270,15 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
         const bool over = nc > kStreamCap && unit_live;
         const int thr = over ? T0 + 1 : kSweepLimit;       // above every score: no bit for the other units
         int above = 0;
-        ks.restart(-thr);
+        // a sweep of this wavefront alone: the keys come straight from memory
+        KeyStream<K, VEC> alone;
+        alone.start(Kh, Qunit, unit_live, lane, Lq, L, -thr);
         for (int w = 0; w < NWL; ++w) {
             unsigned word;
-            if (8 * w + 8 + 2 + PF <= tfull) {
-                word = pass2_word<false, K, VEC>(ks, 8 * w);
+            if (8 * w + 8 + decltype(alone)::kLookahead <= tfull) {
+                word = pass2_word<false, 0>(alone, 8 * w);
             } else {
-                word = pass2_word<true, K, VEC>(ks, 8 * w);
+                word = pass2_word<true, 0>(alone, 8 * w);
                 const int nv = key_lim - (key_lo + 32 * w);
                 word = nv >= 32 ? word : nv <= 0 ? 0u : word & ((1u << nv) - 1u);
             }
@@ -469,9 +513,8 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
 // LDS of one workgroup: per wavefront the bitmap (later the image of the index rows) and the lists.
 size_t stream_words_per_wave(const dsa_shape &sh)
 {
-    const size_t head_words =
-        std::max<size_t>((size_t)(stream_quarter(sh.L) / 32) * kWave, ((size_t)kStreamUnits * sh.keep + 2) / 2);
-    return head_words + (size_t)kStreamUnits * kStreamStride / 2;
+    static_assert(kStreamUnits * kStreamStride % 8 == 0, "every wavefront's part starts on a 16-byte boundary");
+    return (size_t)stream_head_words(sh.L, sh.keep) + (size_t)kStreamUnits * kStreamStride / 2;
 }
 size_t stream_lds_bytes(const dsa_shape &sh) { return sizeof(unsigned) * stream_words_per_wave(sh) * kStreamWaves; }
 
@@ -483,9 +526,9 @@ hipError_t launch_stream_t(const dsa_shape &sh, const int8_t *Qt, const int8_t *
     auto kern = predict_stream<K, VEC, NB>;
     if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
     const int tasks_per_head = (sh.L / VEC + kStreamUnits - 1) / kStreamUnits;
-    const unsigned tasks = (unsigned)sh.B * sh.H * tasks_per_head;
-    hipLaunchKernelGGL(kern, dim3((tasks + kStreamWaves - 1) / kStreamWaves), dim3(kStreamWaves * kWave), lds, st, Qt, Kt,
-                       idx, sh.L, sh.keep, tasks_per_head, tasks, (int)words_per_wave);
+    const int wgs_per_head = (tasks_per_head + kStreamWaves - 1) / kStreamWaves;
+    hipLaunchKernelGGL(kern, dim3((unsigned)sh.B * sh.H * wgs_per_head), dim3(kStreamWaves * kWave), lds, st, Qt, Kt, idx,
+                       sh.L, sh.keep, tasks_per_head, wgs_per_head, (int)words_per_wave);
     return hipGetLastError();
 }
 
@@ -518,6 +561,10 @@ bool stream_predict_fits(const dsa_shape &sh)
 {
     if ((sh.vec != 1 && sh.vec != 4 && sh.vec != 8) || (sh.k != 16 && sh.k != 32 && sh.k != 64)) return false;
     if (sh.L > kStreamMaxL) return false;
+    // Vector-wise masks have few units: with less than one workgroup per compute unit the tiled
+    // kernel, which spreads the keys of a unit over a whole workgroup, is faster (measured).
+    const long long tasks = (long long)sh.B * sh.H * ((sh.L / sh.vec + kStreamUnits - 1) / kStreamUnits);
+    if (sh.vec != 1 && tasks < 4 * 256) return false;
     if (sh.keep > kStreamCap * 5 / 8) return false;     // about 1.25 * keep candidates, with room to spare
     if (4 * stream_buckets(sh.L, stream_nb(sh.L)) < 5 * sh.keep) return false;
     return stream_lds_bytes(sh) <= 160 * 1024;

@@ -26,7 +26,6 @@ __global__ __launch_bounds__(kWave, 4) void threshold_sweep(const int8_t *__rest
                                                            unsigned *__restrict__ bitmap, int32_t *__restrict__ cnt,
                                                            int L, int theta, int tasks_per_head)
 {
-    constexpr int PF = kStreamPrefetch;
     const int lane = threadIdx.x;
     const int c = lane & 15, g = lane >> 4;
     const unsigned task = xcd_contiguous(blockIdx.x, gridDim.x);
@@ -42,16 +41,16 @@ __global__ __launch_bounds__(kWave, 4) void threshold_sweep(const int8_t *__rest
     const int key_lo = g * Lq, key_lim = min(L, key_lo + Lq);
 
     KeyStream<K> ks;
-    ks.start(Kh, Qh + (size_t)min(u0 + c, L - 1) * K, unit_live, lane, Lq, L);
-    ks.restart(-max(-kSweepLimit, min(theta, kSweepLimit)));     // no score lies beyond the limits
+    // no score lies beyond the limits
+    ks.start(Kh, Qh + (size_t)min(u0 + c, L - 1) * K, unit_live, lane, Lq, L, -max(-kSweepLimit, min(theta, kSweepLimit)));
     unsigned *words = bitmap + (size_t)task * NWL * kWave + lane;
     int mine = 0;
     for (int w = 0; w < NWL; ++w) {
         unsigned word;
-        if (8 * w + 8 + 2 + PF <= tfull) {
-            word = pass2_word<false, K, 1>(ks, 8 * w);
+        if (8 * w + 8 + decltype(ks)::kLookahead <= tfull) {
+            word = pass2_word<false, 0>(ks, 8 * w);
         } else {
-            word = pass2_word<true, K, 1>(ks, 8 * w);
+            word = pass2_word<true, 0>(ks, 8 * w);
             const int nv = key_lim - (key_lo + 32 * w);      // real keys in this word
             word = nv >= 32 ? word : nv <= 0 ? 0u : word & ((1u << nv) - 1u);
         }
