@@ -194,8 +194,8 @@ dsa_status dsa_mfma_i8_sustained(int32_t blocks, int32_t iters, int32_t *sink, v
  *     ascending.  row_ptr[last] is the number of kept positions in all.
  * `col` has room for col_capacity entries; entries beyond it are not written, and the caller sees
  * from row_ptr[last] > col_capacity that it has to call again with a larger array.  shape->keep is
- * not used (pass 1).  Built for vec = 1 and k = 16, 32 or 64 (others: DSA_ERR_UNSUPPORTED), and for
- * B*H*L*L <= 2^31 - 1.  `ws`: device scratch of at least dsa_threshold_workspace_bytes(). */
+ * not used (pass 1).  Built for vec = 1, 4 or 8 (the score of a unit is the sum over its vec rows, step
+ * (a2)) and k = 16, 32 or 64 (others: DSA_ERR_UNSUPPORTED), and for B*H*L*L <= 2^31 - 1.  `ws`: device scratch of at least dsa_threshold_workspace_bytes(). */
 size_t dsa_threshold_workspace_bytes(const dsa_shape *shape);
 dsa_status dsa_predict_mask_threshold(const dsa_shape *shape, const int8_t *Qt, const int8_t *Kt, int32_t theta,
                                       int32_t *row_ptr, int32_t *col, int64_t col_capacity, void *ws,

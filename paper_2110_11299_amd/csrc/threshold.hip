@@ -1,6 +1,7 @@
 // Threshold masks (paper section 3.1: the mask may be predicted "using thresholds" instead of a
 // top-k search).  Unit u keeps every key whose approximate score reaches theta; a unit with none
-// keeps its single best key (largest score, lower index among equals).  The count per unit varies,
+// keeps its single best key (largest score, lower index among equals).  A unit is a query row or a
+// group of vec rows whose scores are summed (section 3.3).  The count per unit varies,
 // which is what the paper's equal-count constraint avoids (section 5.2), so the mask is CSR:
 // row_ptr [units + 1], col [nnz], keys ascending per unit.
 //
@@ -21,7 +22,7 @@ constexpr int kScanBlock = 1024;        // units per block of the prefix sum
 
 // Bitmap in the workspace: word w of lane l of task t at (t * NWL + w) * 64 + l (what a wavefront
 // stores with one instruction is contiguous).
-template <int K>
+template <int K, int VEC>
 __global__ __launch_bounds__(kWave, 4) void threshold_sweep(const int8_t *__restrict__ Qt, const int8_t *__restrict__ Kt,
                                                            unsigned *__restrict__ bitmap, int32_t *__restrict__ cnt,
                                                            int L, int theta, int tasks_per_head)
@@ -34,15 +35,17 @@ __global__ __launch_bounds__(kWave, 4) void threshold_sweep(const int8_t *__rest
     const int Lq = stream_quarter(L), NT = Lq / 4, NWL = Lq / 32;
     const int8_t *Kh = Kt + (size_t)n * L * K;
     const int8_t *Qh = Qt + (size_t)n * L * K;
-    const bool unit_live = u0 + c < L;
+    const int G = L / VEC;                  // units of a head
+    const bool unit_live = u0 + c < G;
     int tfull = NT;
 #pragma unroll
     for (int q = 0; q < 4; ++q) tfull = min(tfull, max(0, min(L - q * Lq, Lq)) / 4);
     const int key_lo = g * Lq, key_lim = min(L, key_lo + Lq);
 
-    KeyStream<K> ks;
+    KeyStream<K, VEC> ks;
     // no score lies beyond the limits
-    ks.start(Kh, Qh + (size_t)min(u0 + c, L - 1) * K, unit_live, lane, Lq, L, -max(-kSweepLimit, min(theta, kSweepLimit)));
+    ks.start(Kh, Qh + (size_t)min(u0 + c, G - 1) * (VEC * K), unit_live, lane, Lq, L,
+             -max(-kSweepLimit, min(theta, kSweepLimit)));
     unsigned *words = bitmap + (size_t)task * NWL * kWave + lane;
     int mine = 0;
     for (int w = 0; w < NWL; ++w) {
@@ -59,7 +62,7 @@ __global__ __launch_bounds__(kWave, 4) void threshold_sweep(const int8_t *__rest
     }
     mine += __shfl_xor(mine, 16, kWave);
     mine += __shfl_xor(mine, 32, kWave);
-    if (g == 0 && unit_live) cnt[(size_t)n * L + u0 + c] = max(mine, 1);      // an empty unit keeps one key
+    if (g == 0 && unit_live) cnt[(size_t)n * G + u0 + c] = max(mine, 1);      // an empty unit keeps one key
 }
 
 // Exclusive prefix sums inside blocks of kScanBlock counts (into row_ptr) and the block totals.
@@ -124,13 +127,15 @@ __global__ __launch_bounds__(256) void threshold_fill(const int8_t *__restrict__
                                                       const unsigned *__restrict__ bitmap,
                                                       const int32_t *__restrict__ block_total,
                                                       int32_t *__restrict__ row_ptr, int32_t *__restrict__ col,
-                                                      long long col_capacity, int L, int tasks_per_head, unsigned units)
+                                                      long long col_capacity, int L, int vec, int tasks_per_head,
+                                                      unsigned units)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const unsigned u = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + (threadIdx.x >> 6);
     if (u >= units) return;
-    const unsigned n = u / (unsigned)L;
-    const int i = (int)(u % (unsigned)L);
+    const int G = L / vec;
+    const unsigned n = u / (unsigned)G;
+    const int i = (int)(u % (unsigned)G);
     const int Lq = stream_quarter(L), NWL = Lq / 32, NW = 4 * NWL;
     const unsigned task = n * (unsigned)tasks_per_head + (unsigned)(i >> 4);
     const int c = i & 15;
@@ -157,11 +162,11 @@ __global__ __launch_bounds__(256) void threshold_fill(const int8_t *__restrict__
     }
     if (base == 0) {
         // no key reached theta: the unit keeps its best key (largest score, lower index among equals)
-        const int *qu = reinterpret_cast<const int *>(Qt + ((size_t)n * L + i) * K);
+        const int *qu = reinterpret_cast<const int *>(Qt + ((size_t)n * L + (size_t)i * vec) * K);
         const int8_t *Kh = Kt + (size_t)n * L * K;
         int best = INT32_MIN, at = 0;
         for (int j = lane; j < L; j += kWave) {
-            const int s = unit_key_score(qu, Kh + (size_t)j * K, 1, K / 4);
+            const int s = unit_key_score(qu, Kh + (size_t)j * K, vec, K / 4);
             if (s > best) { best = s; at = j; }          // ascending j per lane: the first maximum stays
         }
         const int top = wave_max(best);
@@ -170,35 +175,47 @@ __global__ __launch_bounds__(256) void threshold_fill(const int8_t *__restrict__
     }
 }
 
-template <int K>
-hipError_t launch_threshold_k(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int theta, int32_t *row_ptr,
+template <int K, int VEC>
+hipError_t launch_threshold_kv(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int theta, int32_t *row_ptr,
                               int32_t *col, long long col_capacity, void *ws, hipStream_t st)
 {
-    const int tasks_per_head = (sh.L + 15) / 16;
+    const int tasks_per_head = (sh.L / VEC + 15) / 16;
     const unsigned tasks = (unsigned)sh.B * sh.H * tasks_per_head;
-    const unsigned units = (unsigned)sh.B * sh.H * sh.L;
+    const unsigned units = (unsigned)sh.B * sh.H * (sh.L / VEC);
     const unsigned blocks = (units + kScanBlock - 1) / kScanBlock;
     const size_t bitmap_words = (size_t)tasks * (stream_quarter(sh.L) / 32) * kWave;
     unsigned *bitmap = static_cast<unsigned *>(ws);
     int32_t *cnt = reinterpret_cast<int32_t *>(bitmap + bitmap_words);
     int32_t *block_total = cnt + units;
-    hipLaunchKernelGGL(threshold_sweep<K>, dim3(tasks), dim3(kWave), 0, st, Qt, Kt, bitmap, cnt, sh.L, theta,
+    hipLaunchKernelGGL((threshold_sweep<K, VEC>), dim3(tasks), dim3(kWave), 0, st, Qt, Kt, bitmap, cnt, sh.L, theta,
                        tasks_per_head);
     hipLaunchKernelGGL(scan_blocks, dim3(blocks), dim3(256), 0, st, cnt, row_ptr, block_total, units);
     hipLaunchKernelGGL(scan_totals, dim3(1), dim3(256), 0, st, block_total, blocks, row_ptr, units);
     hipLaunchKernelGGL(threshold_fill<K>, dim3((units + 3) / 4), dim3(256), 0, st, Qt, Kt, bitmap, block_total, row_ptr,
-                       col, col_capacity, sh.L, tasks_per_head, units);
+                       col, col_capacity, sh.L, VEC, tasks_per_head, units);
     return hipGetLastError();
+}
+
+template <int K>
+hipError_t launch_threshold_k(const dsa_shape &sh, const int8_t *Qt, const int8_t *Kt, int theta, int32_t *row_ptr,
+                              int32_t *col, long long col_capacity, void *ws, hipStream_t st)
+{
+    if (sh.vec == 1) return launch_threshold_kv<K, 1>(sh, Qt, Kt, theta, row_ptr, col, col_capacity, ws, st);
+    if (sh.vec == 4) return launch_threshold_kv<K, 4>(sh, Qt, Kt, theta, row_ptr, col, col_capacity, ws, st);
+    return launch_threshold_kv<K, 8>(sh, Qt, Kt, theta, row_ptr, col, col_capacity, ws, st);
 }
 
 }  // namespace
 
-bool threshold_supported(const dsa_shape &sh) { return sh.vec == 1 && (sh.k == 16 || sh.k == 32 || sh.k == 64); }
+bool threshold_supported(const dsa_shape &sh)
+{
+    return (sh.vec == 1 || sh.vec == 4 || sh.vec == 8) && (sh.k == 16 || sh.k == 32 || sh.k == 64);
+}
 
 size_t threshold_workspace_bytes(const dsa_shape &sh)
 {
-    const size_t tasks = (size_t)sh.B * sh.H * ((sh.L + 15) / 16);
-    const size_t units = (size_t)sh.B * sh.H * sh.L;
+    const size_t tasks = (size_t)sh.B * sh.H * ((sh.L / sh.vec + 15) / 16);
+    const size_t units = (size_t)sh.B * sh.H * (sh.L / sh.vec);
     const size_t blocks = (units + kScanBlock - 1) / kScanBlock;
     return sizeof(unsigned) * tasks * (stream_quarter(sh.L) / 32) * kWave + sizeof(int32_t) * (units + blocks);
 }

@@ -34,12 +34,12 @@ def dev_qkv(x):
 def run_case(pkg, oracle, x, theta, label, capacity=None, check_attention=True):
     import torch
     cfg = x.cfg
-    sh = pkg.make_shape(cfg.B, cfg.H, cfg.L, cfg.d, cfg.k, 1, 1, pkg.DSA_F32 if cfg.dtype == "f32" else pkg.DSA_BF16,
+    sh = pkg.make_shape(cfg.B, cfg.H, cfg.L, cfg.d, cfg.k, 1, cfg.vec, pkg.DSA_F32 if cfg.dtype == "f32" else pkg.DSA_BF16,
                         float(cfg.scale))
-    want_ptr, want_col = oracle.predict_mask_threshold(x.Qt, x.Kt, theta, 1)
+    want_ptr, want_col = oracle.predict_mask_threshold(x.Qt, x.Kt, theta, cfg.vec)
     nnz = int(want_ptr[-1])
     cap = nnz if capacity is None else capacity
-    print(f"[{label}] B={cfg.B} H={cfg.H} L={cfg.L} k={cfg.k} theta={theta}: nnz={nnz} "
+    print(f"[{label}] B={cfg.B} H={cfg.H} L={cfg.L} k={cfg.k} vec={cfg.vec} theta={theta}: nnz={nnz} "
           f"(mean {nnz / (want_ptr.size - 1):.1f}, max {int(np.diff(want_ptr).max())} per row), capacity {cap}", flush=True)
     Qt, Kt = torch.from_numpy(x.Qt).cuda(), torch.from_numpy(x.Kt).cuda()
     guard = 64
@@ -58,7 +58,7 @@ def run_case(pkg, oracle, x, theta, label, capacity=None, check_attention=True):
     O = pkg.dsa_masked_attention_csr(sh, Q, K, V, row_ptr, col)
     torch.cuda.synchronize()
     rows = None if cfg.N * cfg.L <= 70000 else np.arange(0, cfg.N * cfg.L, 13)
-    want_O = oracle.masked_attention_csr(x.Q, x.K, x.V, want_ptr, want_col, cfg.scale, 1, rows=rows)
+    want_O = oracle.masked_attention_csr(x.Q, x.K, x.V, want_ptr, want_col, cfg.scale, cfg.vec, rows=rows)
     got_O = O.cpu().numpy().reshape(-1, cfg.d)
     err = float(np.abs((got_O if rows is None else got_O[rows]) - want_O).max())
     print(f"    max|O - oracle| = {err:.3e}", flush=True)
@@ -67,12 +67,13 @@ def run_case(pkg, oracle, x, theta, label, capacity=None, check_attention=True):
 
 def theta_for(oracle, x, fraction):
     """A threshold that about `fraction` of the scores reach (from a sample of units)."""
-    units = np.arange(0, x.cfg.N * x.cfg.L, max(1, x.cfg.N * x.cfg.L // 256))
-    sc = oracle.approx_scores(x.Qt, x.Kt, 1, units=units)
+    n_units = x.cfg.N * (x.cfg.L // x.cfg.vec)
+    units = np.arange(0, n_units, max(1, n_units // 256))
+    sc = oracle.approx_scores(x.Qt, x.Kt, x.cfg.vec, units=units)
     return int(np.quantile(sc, 1.0 - fraction))
 
 
-@pytest.mark.parametrize("name,fraction", [("C1", 0.10), ("C2", 0.10), ("C4f", 0.05)])
+@pytest.mark.parametrize("name,fraction", [("C1", 0.10), ("C2", 0.10), ("C4f", 0.05), ("C3", 0.05), ("C4v", 0.05)])
 def test_threshold_configs(dsa, oracle, workload, name, fraction):
     x = workload(name)
     run_case(dsa, oracle, x, theta_for(oracle, x, fraction), name)
@@ -85,6 +86,27 @@ RAGGED = [
     dict(B=1, H=1, L=1, d=64, dtype="f32", k=16),
     dict(B=1, H=1, L=5000, d=128, dtype="bf16", k=32, n_global=6),
 ]
+
+
+RAGGED_GROUPS = [
+    dict(B=1, H=3, L=100, d=64, dtype="f32", k=16, vec=4),
+    dict(B=2, H=2, L=776, d=64, dtype="bf16", k=64, vec=8),
+    dict(B=1, H=2, L=1000, d=128, dtype="f32", k=32, vec=8),
+    dict(B=1, H=1, L=4, d=64, dtype="f32", k=16, vec=4),
+    dict(B=1, H=2, L=2052, d=64, dtype="bf16", k=32, vec=4, n_global=6),
+]
+
+
+@pytest.mark.parametrize("spec", RAGGED_GROUPS, ids=lambda s: "-".join(f"{k}{v}" for k, v in s.items()))
+def test_threshold_ragged_vector_wise(dsa, oracle, spec):
+    """Groups of 4 or 8 rows as units (the group score is the sum over the rows): ragged key tails, unit
+    counts that do not fill the last wavefront, a single unit."""
+    cfg = di.custom_config(rank=4, seed=161 + spec["L"], keep=1, **spec)
+    x = di.make_inputs(cfg)
+    for fraction in (0.02, 0.3):
+        run_case(dsa, oracle, x, theta_for(oracle, x, fraction), "ragged groups")
+    sc = oracle.approx_scores(x.Qt, x.Kt, cfg.vec)
+    run_case(dsa, oracle, x, int(sc.max()) + 1, "no key reaches theta: best key per group")
 
 
 @pytest.mark.parametrize("spec", RAGGED, ids=lambda s: "-".join(f"{k}{v}" for k, v in s.items()))
@@ -120,7 +142,7 @@ def test_threshold_errors_launch_nothing(dsa):
     b = dsa.binding
     lib = b.lib()
     fake = ctypes.c_void_p(0x1000)
-    sh = b.make_shape(1, 2, 256, 64, 32, 1, 8, b.DSA_F32, 0.125)
+    sh = b.make_shape(1, 2, 256, 64, 32, 1, 2, b.DSA_F32, 0.125)
     assert lib.dsa_predict_mask_threshold(ctypes.byref(sh), fake, fake, 0, fake, fake, 10, fake, 1 << 30, None) == 3
     assert b.threshold_workspace_bytes(sh) == 0
     sh = b.make_shape(1, 2, 256, 64, 32, 1, 1, b.DSA_F32, 0.125)
