@@ -126,6 +126,8 @@ def main() -> int:
         for _ in range(3):
             pkg.dsa_approx_rowmax(passes[0]["sh"], Qt, Kt, rowmax=rm)
         pkg.binding.dsa_gather_roof(passes[0]["sh"], K, V, passes[0]["idx"])
+        # nothing but int8 matrix instructions: what the matrix-core busy counter reads when the cores are full
+        pkg.dsa_mfma_i8_sustained(2048, 512, torch.empty(2048 * 256, dtype=torch.int32, device="cuda"))
         src = torch.empty(PMC_COPY_BYTES, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
         dst.copy_(src)          # reads and writes PMC_COPY_BYTES each
@@ -248,10 +250,10 @@ def main() -> int:
     dom = stages["C4f"]
     scores_per_launch = float(cf.N) * cf.L * cf.L
     achieved_alu = scores_per_launch / (dom["predict_ms"] * 1e-3) / 1e12
-    roofline = dict(kernel="predict_stream<32, 128> (fine-grained dsa_predict_mask at C4: a1 + b)", bound="alu",
+    roofline = dict(kernel="predict_stream<32, 1, 128> (fine-grained dsa_predict_mask at C4: a1 + b)", bound="alu",
                     achieved=achieved_alu, peak=ALU_PEAK_LANE_OPS / 1e12, unit="Tlane-op/s",
                     frac=achieved_alu / (ALU_PEAK_LANE_OPS / 1e12),
-                    traffic=profiled_traffic_bytes("predict_stream<32, 128>"),
+                    traffic=profiled_traffic_bytes("predict_stream<32, 1, 128>"),
                     traffic_source="profiles/bench_C4_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run)",
                     algorithmic_ops=scores_per_launch, algorithmic_unit="score inspections (N*L*L), one lane operation each",
                     avg_launch_ms=dom["predict_ms"], int8_TOPS=dom["predict_int8_TOPS"],

@@ -320,10 +320,13 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
             // one bit per trip and lane, no branch inside: a lane with nothing left (or no room) writes
             // to the spare slot behind its unit's list
             while (__ballot(m != 0u) != 0) {
-                const bool put = m != 0u && pos < kStreamCap;
-                list[put ? pos : kStreamCap] = (uint16_t)(key1 + __ffs(m));
-                pos += m != 0u;
-                m &= m - 1u;
+#pragma unroll
+                for (int twice = 0; twice < 2; ++twice) {       // two bits per test of the wavefront
+                    const bool put = m != 0u && pos < kStreamCap;
+                    list[put ? pos : kStreamCap] = (uint16_t)(key1 + __ffs(m));
+                    pos += m != 0u;
+                    m &= m - 1u;
+                }
             }
         }
     }
