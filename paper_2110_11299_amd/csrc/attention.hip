@@ -11,10 +11,13 @@
 #include "dsa_internal.h"
 #include "attention_api.h"
 
+#include <type_traits>
+
 namespace dsa {
 namespace {
 
 constexpr int kRowWaves = 4;          // query rows (wavefronts) per workgroup
+constexpr int kRowPad = 8;            // the row kernel pads a key list to a multiple of this
 constexpr int kMaxKeep = 4096;        // list and scores of a row in LDS: 4 waves * 4096 * 8 B = 128 KB
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -30,10 +33,15 @@ template <> struct Piece<float> {
     {
         return fmaf(a.w, b.w, fmaf(a.z, b.z, fmaf(a.y, b.y, a.x * b.x)));
     }
-    static __device__ __forceinline__ void axpy(float (&o)[4], float p, raw_t b)
+    // A weight as the word that is kept in LDS, the sum of weights, o += weight * b, and -a.
+    static __device__ __forceinline__ unsigned weight(float p) { return __float_as_uint(p); }
+    static __device__ __forceinline__ float wsum(float z, unsigned w) { return z + __uint_as_float(w); }
+    static __device__ __forceinline__ void axpy(float (&o)[4], unsigned w, raw_t b)
     {
+        const float p = __uint_as_float(w);
         o[0] = fmaf(p, b.x, o[0]); o[1] = fmaf(p, b.y, o[1]); o[2] = fmaf(p, b.z, o[2]); o[3] = fmaf(p, b.w, o[3]);
     }
+    static __device__ __forceinline__ raw_t negate(raw_t a) { return make_float4(-a.x, -a.y, -a.z, -a.w); }
 };
 // bfloat16: v_dot2_f32_bf16 multiplies two packed pairs and accumulates in fp32, so no element is
 // ever unpacked.  For the weighted sum the weight is rounded to bfloat16 (relative 2^-9, inside the
@@ -50,9 +58,17 @@ template <> struct Piece<uint16_t> {
     {
         return dot2(a.w, b.w, dot2(a.z, b.z, dot2(a.y, b.y, dot2(a.x, b.x, 0.f))));
     }
-    static __device__ __forceinline__ void axpy(float (&o)[8], float p, raw_t b)
+    // The weight kept in LDS is the pair (p rounded to bfloat16, 0); the sum takes the rounded weights, the
+    // ones the products use.
+    static __device__ __forceinline__ unsigned weight(float p) { return __builtin_bit_cast(unsigned short, (__bf16)p); }
+    static __device__ __forceinline__ float wsum(float z, unsigned w) { return dot2(w, 0x3f803f80u, z); }
+    static __device__ __forceinline__ raw_t negate(raw_t a)
     {
-        const unsigned lo = __builtin_bit_cast(unsigned short, (__bf16)p), hi = lo << 16;
+        return make_uint4(a.x ^ 0x80008000u, a.y ^ 0x80008000u, a.z ^ 0x80008000u, a.w ^ 0x80008000u);
+    }
+    static __device__ __forceinline__ void axpy(float (&o)[8], unsigned lo, raw_t b)
+    {
+        const unsigned hi = lo << 16;
         o[0] = dot2(b.x, lo, o[0]); o[1] = dot2(b.x, hi, o[1]);
         o[2] = dot2(b.y, lo, o[2]); o[3] = dot2(b.y, hi, o[3]);
         o[4] = dot2(b.z, lo, o[4]); o[5] = dot2(b.z, hi, o[5]);
@@ -124,7 +140,7 @@ template <typename T, int D, int MODE>
 __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const int32_t *__restrict__ idx, const float *__restrict__ Pin, float *__restrict__ S,
-    float *__restrict__ O, int L, int keep, int vec, float scale, unsigned total_rows)
+    float *__restrict__ O, int L, int keep, int keep_pad, int vec, float scale, unsigned total_rows)
 {
     typedef Piece<T> P;
     constexpr int E = P::N;               // elements per lane
@@ -141,44 +157,61 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
     const unsigned r = live ? row : total_rows - 1;      // dead waves shadow a real row, write nothing
     const unsigned n = r / (unsigned)L, i = r % (unsigned)L;
     const int32_t *list = idx + ((size_t)n * (L / vec) + i / vec) * keep;
-    // per wavefront in LDS: the row's key list (clamped into [0, L), so that no idx can send a
-    // gather outside K / V) and, in the fused mode, its scores
-    int *sl = reinterpret_cast<int *>(lds_scores) + wave * (MODE == kFused ? 2 : 1) * keep;
-    float *sc = reinterpret_cast<float *>(sl + keep);
-    for (int t = lane; t < keep; t += kWave) sl[t] = min(max(list[t], 0), L - 1);
+    // per wavefront in LDS: the row's key list, as the byte offset of every key row inside its head
+    // (keys clamped into [0, L), so that no idx can send a gather outside K / V), and, in the fused
+    // mode, its scores, later its weights.  The list is padded to keep_pad, a multiple of the keys one
+    // trip of the loops below takes, with its last key: a padded entry has the score of a real one (no
+    // effect on the maximum) and gets the weight 0, so the loops test nothing.
+    constexpr unsigned kRowBytes = D * sizeof(T), kPieceBytes = E * sizeof(T);
+    unsigned *sl = reinterpret_cast<unsigned *>(lds_scores) + wave * (MODE == kFused ? 2 : 1) * keep_pad;
+    float *sc = reinterpret_cast<float *>(sl + keep_pad);
+    unsigned *sw = reinterpret_cast<unsigned *>(sc);      // the same words once they hold weights
+    for (int t = lane; t < keep_pad; t += kWave) sl[t] = (unsigned)min(max(list[min(t, keep - 1)], 0), L - 1) * kRowBytes;
     wave_lds_fence();
     constexpr int U = 4;                  // independent gathers in flight per lane
+    static_assert(kRowPad % RPI == 0, "keep_pad is a whole number of single trips");
+    const unsigned piece_at = sub * kPieceBytes;
+    auto piece_of = [&](const T *head, unsigned row_at) {
+        return P::load(reinterpret_cast<const T *>(reinterpret_cast<const char *>(head) + (size_t)(row_at + piece_at)));
+    };
 
     float m = -INFINITY;
+    // fused mode: the scores are kept as sign(scale) * q.k and the factor |scale| waits for the exponential
+    const bool flip = MODE == kFused && scale < 0.f;
+    const float factor = MODE == kFused ? fabsf(scale) : scale;
     if (MODE != kSpmm) {
-        const typename P::raw_t q = P::load(Q + (size_t)r * D + sub * E);
+        typename P::raw_t q = P::load(Q + (size_t)r * D + sub * E);
+        if (flip) q = P::negate(q);
         const T *Kh = K + (size_t)n * L * D;
-        for (int t0 = 0; t0 < keep; t0 += U * RPI) {
-            typename P::raw_t kv[U];
+        // UU gathers in flight per lane: trips of U while they fit, single ones for the rest
+        auto scores_of = [&](int t0, auto uu) {
+            constexpr int UU = decltype(uu)::value;
+            typename P::raw_t kv[UU];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int j = sl[min(t0 + u * RPI + grp, keep - 1)];
-                kv[u] = P::load(Kh + (unsigned)(j * D + sub * E));
-            }
+            for (int u = 0; u < UU; ++u) kv[u] = piece_of(Kh, sl[t0 + u * RPI + grp]);
+            float acc[UU];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
+            for (int u = 0; u < UU; ++u) acc[u] = piece_sum<LPR>(P::dot(q, kv[u]));
+#pragma unroll
+            for (int u = 0; u < UU; ++u) {
                 const int t = t0 + u * RPI + grp;
-                const float acc = piece_sum<LPR>(P::dot(q, kv[u])) * scale;
-                if (t < keep) {
-                    m = fmaxf(m, acc);
-                    if (sub == 0) {
-                        if (MODE == kSddmm) { if (live) S[(size_t)r * keep + t] = acc; }
-                        else sc[t] = acc;
-                    }
+                if (MODE == kSddmm) {
+                    if (sub == 0 && live && t < keep) S[(size_t)r * keep + t] = acc[u] * factor;
+                } else {
+                    m = fmaxf(m, acc[u]);
+                    sc[t] = acc[u];           // every lane of the group writes the same value
                 }
             }
-        }
+        };
+        int t0 = 0;
+        for (; t0 + U * RPI <= keep_pad; t0 += U * RPI) scores_of(t0, std::integral_constant<int, U>{});
+        for (; t0 < keep_pad; t0 += RPI) scores_of(t0, std::integral_constant<int, 1>{});
         if (MODE == kSddmm) return;
         m = groups_max<LPR>(m);
         wave_lds_fence();
         // unnormalised weights, computed once per kept key (the lanes that share a value row would
-        // otherwise each repeat the exponential)
-        for (int t = lane; t < keep; t += kWave) sc[t] = __expf(sc[t] - m);
+        // otherwise each repeat the exponential), in the form the products take them
+        for (int t = lane; t < keep_pad; t += kWave) sw[t] = t < keep ? P::weight(__expf(factor * (sc[t] - m))) : 0u;
         wave_lds_fence();
     }
 
@@ -186,23 +219,27 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] = 0.f;
     const T *Vh = V + (size_t)n * L * D;
-    for (int t0 = 0; t0 < keep; t0 += U * RPI) {
-        typename P::raw_t vv[U];
-        float p[U];
+    auto values_of = [&](int t0, auto uu) {
+        constexpr int UU = decltype(uu)::value;
+        typename P::raw_t vv[UU];
+        unsigned w[UU];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
+        for (int u = 0; u < UU; ++u) {
             const int t = t0 + u * RPI + grp;
-            const int tt = min(t, keep - 1);
-            vv[u] = P::load(Vh + (unsigned)(sl[tt] * D + sub * E));
-            if (MODE == kSpmm) p[u] = Pin[(size_t)r * keep + tt];
-            else p[u] = sc[tt];
-            p[u] = t < keep ? p[u] : 0.f;
+            vv[u] = piece_of(Vh, sl[t]);
+            if (MODE == kSpmm) w[u] = t < keep ? P::weight(Pin[(size_t)r * keep + t]) : 0u;
+            else w[u] = sw[t];
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            z += p[u];
-            P::axpy(o, p[u], vv[u]);
+        for (int u = 0; u < UU; ++u) {
+            z = P::wsum(z, w[u]);
+            P::axpy(o, w[u], vv[u]);
         }
+    };
+    {
+        int t0 = 0;
+        for (; t0 + U * RPI <= keep_pad; t0 += U * RPI) values_of(t0, std::integral_constant<int, U>{});
+        for (; t0 < keep_pad; t0 += RPI) values_of(t0, std::integral_constant<int, 1>{});
     }
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] = groups_sum<LPR>(o[e]);
@@ -295,7 +332,7 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows_csr(
 #pragma unroll
             for (int x = 0; x < U; ++x) {
                 z += p[x];
-                P::axpy(o, p[x], vv[x]);
+                P::axpy(o, P::weight(p[x]), vv[x]);
             }
         }
         wave_lds_fence();                                  // the next chunk overwrites list and scores
@@ -320,11 +357,12 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows_csr(
 template <typename T, int D>
 __global__ __launch_bounds__(kRowWaves *kWave) void gather_probe(const T *__restrict__ K, const T *__restrict__ V,
                                                                  const int32_t *__restrict__ idx,
-                                                                 unsigned *__restrict__ sink, int L, int keep, int vec,
-                                                                 unsigned total_rows)
+                                                                 unsigned *__restrict__ sink, int L, int keep,
+                                                                 int keep_pad, int vec, unsigned total_rows)
 {
     typedef Piece<T> P;
     constexpr int E = P::N, LPR = D / E, RPI = kWave / LPR, U = 4;
+    constexpr unsigned kRowBytes = D * sizeof(T), kPieceBytes = E * sizeof(T);
     extern __shared__ float lds_scores[];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -334,23 +372,31 @@ __global__ __launch_bounds__(kRowWaves *kWave) void gather_probe(const T *__rest
     const unsigned r = live ? row : total_rows - 1;
     const unsigned n = r / (unsigned)L, i = r % (unsigned)L;
     const int32_t *list = idx + ((size_t)n * (L / vec) + i / vec) * keep;
-    int *sl = reinterpret_cast<int *>(lds_scores) + wave * keep;
-    for (int t = lane; t < keep; t += kWave) sl[t] = min(max(list[t], 0), L - 1);
+    // the same padded list of byte offsets as in attention_rows, the same address arithmetic
+    unsigned *sl = reinterpret_cast<unsigned *>(lds_scores) + wave * keep_pad;
+    for (int t = lane; t < keep_pad; t += kWave) sl[t] = (unsigned)min(max(list[min(t, keep - 1)], 0), L - 1) * kRowBytes;
     wave_lds_fence();
+    const unsigned piece_at = sub * kPieceBytes;
     unsigned acc = 0;
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
         const T *Xh = (pass ? V : K) + (size_t)n * L * D;
-        for (int t0 = 0; t0 < keep; t0 += U * RPI) {
-            typename P::raw_t x[U];
+        auto gather = [&](int t0, auto uu) {
+            constexpr int UU = decltype(uu)::value;
+            typename P::raw_t x[UU];
 #pragma unroll
-            for (int u = 0; u < U; ++u) x[u] = P::load(Xh + (unsigned)(sl[min(t0 + u * RPI + grp, keep - 1)] * D + sub * E));
+            for (int u = 0; u < UU; ++u)
+                x[u] = P::load(reinterpret_cast<const T *>(reinterpret_cast<const char *>(Xh) +
+                                                           (size_t)(sl[t0 + u * RPI + grp] + piece_at)));
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
+            for (int u = 0; u < UU; ++u) {
                 const uint4 w = __builtin_bit_cast(uint4, x[u]);
                 acc ^= (w.x ^ w.y) ^ (w.z ^ w.w);
             }
-        }
+        };
+        int t0 = 0;
+        for (; t0 + U * RPI <= keep_pad; t0 += U * RPI) gather(t0, std::integral_constant<int, U>{});
+        for (; t0 < keep_pad; t0 += RPI) gather(t0, std::integral_constant<int, 1>{});
     }
     if (live) sink[(size_t)r * kWave + lane] = acc;
 }
@@ -580,24 +626,25 @@ hipError_t launch_rows(AttnMode mode, const dsa_shape &sh, const void *Q, const 
 {
     const unsigned rows = (unsigned)sh.B * sh.H * sh.L;
     const dim3 grid((rows + kRowWaves - 1) / kRowWaves), block(kRowWaves * kWave);
-    // per wavefront: the key list, plus the scores in the fused mode
-    const size_t lds = (size_t)kRowWaves * sh.keep * sizeof(float) * (mode == kFused ? 2 : 1);
+    // per wavefront: the padded key list, plus the scores in the fused mode
+    const int keep_pad = (sh.keep + kRowPad - 1) / kRowPad * kRowPad;
+    const size_t lds = (size_t)kRowWaves * keep_pad * sizeof(float) * (mode == kFused ? 2 : 1);
     const T *q = static_cast<const T *>(Q), *k = static_cast<const T *>(K), *v = static_cast<const T *>(V);
     if (mode == kFused) {
         auto kern = attention_rows<T, D, kFused>;
         if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
-        hipLaunchKernelGGL(kern, grid, block, lds, st, q, k, v, idx, Pin, S, O, sh.L, sh.keep, sh.vec,
+        hipLaunchKernelGGL(kern, grid, block, lds, st, q, k, v, idx, Pin, S, O, sh.L, sh.keep, keep_pad, sh.vec,
                            sh.scale, rows);
     } else if (mode == kSddmm) {
         auto kern = attention_rows<T, D, kSddmm>;
         if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
-        hipLaunchKernelGGL(kern, grid, block, lds, st, q, k, v, idx, Pin, S, O, sh.L, sh.keep, sh.vec, sh.scale,
-                           rows);
+        hipLaunchKernelGGL(kern, grid, block, lds, st, q, k, v, idx, Pin, S, O, sh.L, sh.keep, keep_pad, sh.vec,
+                           sh.scale, rows);
     } else {
         auto kern = attention_rows<T, D, kSpmm>;
         if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
-        hipLaunchKernelGGL(kern, grid, block, lds, st, q, k, v, idx, Pin, S, O, sh.L, sh.keep, sh.vec, sh.scale,
-                           rows);
+        hipLaunchKernelGGL(kern, grid, block, lds, st, q, k, v, idx, Pin, S, O, sh.L, sh.keep, keep_pad, sh.vec,
+                           sh.scale, rows);
     }
     return hipGetLastError();
 }
@@ -637,7 +684,7 @@ hipError_t launch_groups_d(AttnMode mode, const dsa_shape &sh, const void *Q, co
 
 int attention_max_keep() { return kMaxKeep; }
 
-// The row kernel forms element offsets inside one head (key index * d) in 32-bit arithmetic.
+// The row kernel forms byte offsets inside one head (key index * bytes of a row, at most 512) in 32-bit arithmetic.
 int attention_max_L() { return 1 << 22; }
 
 hipError_t launch_attention(AttnMode mode, const dsa_shape &sh, const void *Q, const void *K,
@@ -679,10 +726,11 @@ hipError_t launch_gather_probe(const dsa_shape &sh, const void *K, const void *V
 {
     const unsigned rows = (unsigned)sh.B * sh.H * sh.L;
     const dim3 grid((rows + kRowWaves - 1) / kRowWaves), block(kRowWaves * kWave);
-    const size_t lds = (size_t)kRowWaves * sh.keep * sizeof(int);
+    const int keep_pad = (sh.keep + kRowPad - 1) / kRowPad * kRowPad;
+    const size_t lds = (size_t)kRowWaves * keep_pad * sizeof(int);
     auto go = [&](auto kern, auto *k, auto *v) -> hipError_t {
         if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds)) return e;
-        hipLaunchKernelGGL(kern, grid, block, lds, st, k, v, idx, sink, sh.L, sh.keep, sh.vec, rows);
+        hipLaunchKernelGGL(kern, grid, block, lds, st, k, v, idx, sink, sh.L, sh.keep, keep_pad, sh.vec, rows);
         return hipGetLastError();
     };
     if (sh.dtype == DSA_F32) {
