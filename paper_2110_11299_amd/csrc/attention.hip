@@ -467,32 +467,37 @@ __global__ __launch_bounds__(2 * kGroupWaves *kWave) void attention_groups_bf16(
     for (int t = lane; t < keep_pad; t += kWave) sl[t] = min(max(list[min(t, keep - 1)], 0), L - 1);
     wave_lds_fence();
 
-    // scores of all kept keys -> LDS, running maximum per query.  A ring of PF tiles of key rows is
-    // kept in flight: the rows of tile t + PF are requested as soon as tile t has been consumed.
+    // scores of all kept keys -> LDS, running maximum per query.  The key rows of a step (32 keys) are
+    // gathered the way the value rows are below: D / 8 neighbouring lanes fetch one row as 16-byte pieces
+    // (whole cache lines per row, which is what the vector memory path serves best; fetched straight
+    // into the operand layout, 16 lanes take 16 bytes of 16 different rows each and the same bytes come
+    // at a third of the rate), pass through the value tile's LDS and come back as the first operand of
+    // the matrix instruction.  The rows of step t + 1 are requested before step t is consumed.
     float mx = -INFINITY;
-    constexpr int PF = 1;          // deeper rings measured no faster
+    constexpr int VP = 32 / RPI;           // load instructions per step of 32 rows
+    const int vrow = lane / LPR, vpiece = lane % LPR;
     if (MODE != kSpmm) {
-    bf16x8 kring[PF][KS];
+        v4u kring[VP];
 #pragma unroll
-    for (int p = 0; p < PF; ++p) {
-        const uint16_t *krow = Kh + (size_t)sl[min(16 * p, keep_pad - 16) + c] * D + 8 * g;
+        for (int rr = 0; rr < VP; ++rr)
+            kring[rr] = *reinterpret_cast<const v4u *>(Kh + (size_t)sl[rr * RPI + vrow] * D + vpiece * 8);
+        for (int t0 = 0; t0 < keep_pad; t0 += 32) {
 #pragma unroll
-        for (int s = 0; s < KS; ++s)
-            kring[p][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const v4u *>(krow + 32 * s));
-    }
-    for (int t0 = 0; t0 < keep_pad; t0 += 16 * PF) {
+            for (int rr = 0; rr < VP; ++rr) *reinterpret_cast<v4u *>(sV + (rr * RPI + vrow) * VROW + vpiece * 16) = kring[rr];
+            const int tn = min(t0 + 32, keep_pad - 32);
 #pragma unroll
-        for (int p = 0; p < PF; ++p) {
-            const int tile = t0 + 16 * p;
-            if (tile < keep_pad) {
+            for (int rr = 0; rr < VP; ++rr)
+                kring[rr] = *reinterpret_cast<const v4u *>(Kh + (size_t)sl[tn + rr * RPI + vrow] * D + vpiece * 8);
+            wave_lds_fence();
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int tile = t0 + 16 * half;
                 v4f acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int s = 0; s < KS; ++s)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kring[p][s], qop[s], acc, 0, 0, 0);
-                const uint16_t *krow = Kh + (size_t)sl[min(tile + 16 * PF, keep_pad - 16) + c] * D + 8 * g;
-#pragma unroll
-                for (int s = 0; s < KS; ++s)
-                    kring[p][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const v4u *>(krow + 32 * s));
+                for (int s = 0; s < KS; ++s) {
+                    const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(sV + (16 * half + c) * VROW + (32 * s + 8 * g) * 2);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qop[s], acc, 0, 0, 0);
+                }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     acc[i] = tile + 4 * g + i < keep ? acc[i] * scale : -INFINITY;
@@ -500,8 +505,8 @@ __global__ __launch_bounds__(2 * kGroupWaves *kWave) void attention_groups_bf16(
                 }
                 if (c < 8) *reinterpret_cast<v4f *>(sS + c * keep_pad + tile + 4 * g) = acc;
             }
+            wave_lds_fence();       // the next step overwrites the tile
         }
-    }
     }
     if (MODE == kSddmm) {
         // the 8 rows of scores leave through LDS: consecutive lanes write consecutive entries of a row
@@ -533,9 +538,7 @@ __global__ __launch_bounds__(2 * kGroupWaves *kWave) void attention_groups_bf16(
     float z = 0.f;
     const float *srow = sS + (c & 7) * keep_pad + 4 * g;
     // value rows of a step: 32 / RPI pieces of 16 bytes per lane; a ring of VF steps is kept in flight
-    constexpr int VP = 32 / RPI;
     constexpr int VF = 1;
-    const int vrow = lane / LPR, vpiece = lane % LPR;
     v4u vring[VF][VP];
 #pragma unroll
     for (int f = 0; f < VF; ++f)
