@@ -40,6 +40,27 @@ PMC_COPY_BYTES = 256 << 20   # size of the calibration copy in --pmc-mode
 TRAFFIC_SUMMARY = ROOT / "profiles" / "bench_C4_hbm_traffic.md"
 
 
+COUNTER_SUMMARY = ROOT / "profiles" / "bench_C4_pmc_counters.md"
+
+
+def profiled_ratio(row_prefix: str, kernel_prefix: str):
+    """A cell of the derived-ratio table in the tracked counter summary (row by the start of its label,
+    column by the start of the kernel's name); None if the file, the row or the column is missing."""
+    try:
+        header = None
+        for line in COUNTER_SUMMARY.read_text().splitlines():
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if cells and cells[0] == "ratio":
+                header = [c.strip("`") for c in cells]
+            elif header and cells[0].startswith(row_prefix):
+                for name, cell in zip(header[1:], cells[1:]):
+                    if name.startswith(kernel_prefix):
+                        return float(cell)
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def profiled_traffic_bytes(kernel_prefix: str):
     """Total HBM bytes per launch of the first kernel whose name starts with kernel_prefix in the
     tracked FETCH_SIZE / WRITE_SIZE summary; None if the file or the row is missing."""
@@ -255,6 +276,9 @@ def main() -> int:
                     frac=achieved_alu / (ALU_PEAK_LANE_OPS / 1e12),
                     traffic=profiled_traffic_bytes("predict_stream<32, 1, 128>"),
                     traffic_source="profiles/bench_C4_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run)",
+                    valu_busy=profiled_ratio("vector ALU busy", "predict_stream<32, 1, 128>"),
+                    mfma_busy=profiled_ratio("matrix-core busy", "predict_stream<32, 1, 128>"),
+                    busy_source="profiles/bench_C4_pmc_counters.md (share of the launch in which the vector ALUs / the matrix cores issue; not measured in this run)",
                     algorithmic_ops=scores_per_launch, algorithmic_unit="score inspections (N*L*L), one lane operation each",
                     avg_launch_ms=dom["predict_ms"], int8_TOPS=dom["predict_int8_TOPS"],
                     frac_int8=dom["predict_frac_int8"], share_of_step=dom["predict_ms"] / ms_per_step)
