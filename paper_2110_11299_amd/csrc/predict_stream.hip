@@ -207,6 +207,57 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
         // Invariant: count(maxima >= lo) >= keep, count(maxima >= hi + 1) < keep.  A unit is done when
         // lo == hi, or as soon as a probe lands within `slack` of keep.
         const int slack = keep >> 4;
+        // First a histogram: the unit's range [lo, hi] is cut into at most 128 equal bins, every lane adds
+        // its maxima with LDS atomics (5 operations per value, where a round of the bisection takes 2 per
+        // value and about ten rounds are needed), and the bin in which the count from the top reaches
+        // keep becomes the new range: usually narrow enough to end the search at once.  The bins lie where
+        // the lists will be (the sweeps' staging buffers, idle between the two sweeps).
+        {
+            constexpr int HB = 128;                      // bins per unit
+            constexpr int HS = HB + 4;                   // words from unit to unit: the units' bins start in different banks
+            static_assert(kStreamUnits * HS <= kStreamUnits * kStreamStride / 2, "the bins fit the list area");
+            unsigned *hist = smem + head_words;          // [16 units][HS]
+            const unsigned range = (unsigned)(hi - lo);
+            const int shift = max(0, 25 - (int)__clz((int)(range | 1u)));        // range >> shift < HB
+#pragma unroll
+            for (int i = 0; i < (kStreamUnits * HS / 4 + kWave - 1) / kWave; ++i)
+                if (i * kWave + lane < kStreamUnits * HS / 4) reinterpret_cast<v4i *>(hist)[i * kWave + lane] = v4i{0, 0, 0, 0};
+            wave_lds_sync();
+            unsigned *unit_hist = hist + c * HS;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) atomicAdd(&unit_hist[(unsigned)(max(bmax[b], lo) - lo) >> shift], 1u);
+            wave_lds_sync();
+            // lane (c, g) walks bins 32 g + 31 .. 32 g of its unit from the top
+            v4i part[HB / 16];
+            int total = 0;
+#pragma unroll
+            for (int i = 0; i < HB / 16; ++i) {
+                part[i] = reinterpret_cast<const v4i *>(unit_hist + (HB / 4) * g)[i];
+                total += part[i][0] + part[i][1] + part[i][2] + part[i][3];
+            }
+            // maxima in the bins of the lanes above this one
+            const int t1 = __shfl_xor(total, 16, kWave), t2 = __shfl_xor(total, 32, kWave), t3 = __shfl_xor(t1, 32, kWave);
+            int cum = ((g & 1) ? 0 : t1) + ((g & 2) ? 0 : t2 + t3);       // lanes g ^ 1, g ^ 2, g ^ 3 that lie above g
+            int found = -1, at = 0, before = 0;          // highest bin of this lane at which the count reaches keep
+#pragma unroll
+            for (int j = HB / 4 - 1; j >= 0; --j) {
+                const int next = cum + part[j / 4][j % 4];
+                const bool here = found < 0 && next >= keep;
+                found = here ? (HB / 4) * g + j : found;
+                at = here ? next : at;
+                before = here ? cum : before;
+                cum = next;
+            }
+            const int best = unit_max(found);            // >= 0: all maxima lie at or above lo
+            const bool owner = found == best;            // one lane of the unit
+            const int count_at = unit_sum(owner ? at : 0), count_above = unit_sum(owner ? before : 0);
+            (void)count_above;                           // < keep by construction: the invariant of hi
+            const int new_lo = lo + (best << shift);
+            hi = min(hi, new_lo + (1 << shift) - 1);
+            lo = new_lo;
+            if (count_at - keep <= slack) hi = lo;
+            wave_lds_sync();
+        }
         while (__ballot(lo < hi) != 0) {
             const int mid = (lo + hi + 1) >> 1;     // == lo for a finished unit
             int cnt = 0;
@@ -224,6 +275,7 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
     // ---- pass 2: bitmap of candidates (score >= T0) ----------------------------------------------
     int mine = 0;                                // candidates in this lane's quarter
     {
+        ks.finish();            // every wavefront is through with its bins: the buffers are the sweeps' again
         ks.restart(-T0);
         constexpr int LA = decltype(ks)::kLookahead;
         auto sweep_word = [&](int w, auto par, auto checked) {
