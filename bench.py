@@ -98,6 +98,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--no-all-configs", action="store_true",
                     help="skip timing every stage on the other workload configs ('all_configs' is then null)")
+    ap.add_argument("--no-low-precision", action="store_true",
+                    help="skip the INT4 / INT2 predictor (for a kernel trace in which the dominant kernel is launched "
+                         "on the int8 workload only; 'low_precision_predict' is then empty)")
     ap.add_argument("--pmc-mode", action="store_true",
                     help="for rocprofv3 --pmc runs: a few steps plus one plain device copy of known size "
                          "(calibrates FETCH_SIZE / WRITE_SIZE), no other output")
@@ -170,13 +173,16 @@ def main() -> int:
 
     # Per-kernel durations, same kernels and launch shapes, HIP events on the launch stream.
     def timed(fn, reps):
-        evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
-        evs[0].record()
-        for i in range(reps):
+        """Average duration of one call in a run of reps back-to-back calls on the launch stream (one pair of
+        HIP events around the run: an event between two launches would add its own gap to each)."""
+        fn()
+        first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        first.record()
+        for _ in range(reps):
             fn()
-            evs[i + 1].record()
+        last.record()
         torch.cuda.synchronize()
-        return sum(evs[i].elapsed_time(evs[i + 1]) for i in range(reps)) / reps   # ms
+        return first.elapsed_time(last) / reps   # ms
 
     reps = max(args.steps, 5)
 
@@ -220,7 +226,7 @@ def main() -> int:
     project_ms = timed(project_both, reps)
     # the predictor at the paper's lower precisions (packed INT4 / INT2 codes made on the GPU)
     low_precision = {}
-    for bits in (4, 2):
+    for bits in (() if args.no_low_precision else (4, 2)):
         q_lp, _ = pkg.dsa_project_quantize_bits(sh_f, bits, Q, Rd, ws=pws, want_amax=False)
         k_lp, _ = pkg.dsa_project_quantize_bits(sh_f, bits, K, Rd, ws=pws, want_amax=False)
         ws_lp = torch.empty(pkg.binding.predict_workspace_bytes_bits(sh_f, bits), dtype=torch.uint8, device="cuda")
