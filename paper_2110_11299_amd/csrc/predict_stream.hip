@@ -558,9 +558,26 @@ __global__ __launch_bounds__(kStreamWaves *kWave, 2) void predict_stream(const i
     {
         int32_t *out = idx + ((size_t)n * G + u0) * keep;
         const unsigned fit_units = (unsigned)__ballot(fits && g == 0);      // bit = unit
-        for (int uu = 0; uu < nu; ++uu) {
-            if (!((fit_units >> uu) & 1u) || !task_live) continue;
-            for (int e = lane; e < keep; e += kWave) out[uu * keep + e] = (int)rows[uu * keep + e];
+        const unsigned all_units = nu >= 32 ? ~0u : (1u << nu) - 1u;
+        if ((fit_units & all_units) == all_units) {
+            // the usual case: one block of nu * keep indices, four per lane and store
+            const int total = nu * keep;
+            if (task_live) {
+                for (int e = 4 * lane; e < total; e += 4 * kWave) {
+                    const uint2 four = *reinterpret_cast<const uint2 *>(rows + e);      // the image has slack behind it
+                    const int v[4] = {(int)(four.x & 0xffffu), (int)(four.x >> 16), (int)(four.y & 0xffffu), (int)(four.y >> 16)};
+                    if (e + 4 <= total) {
+                        *reinterpret_cast<int4 *>(out + e) = make_int4(v[0], v[1], v[2], v[3]);
+                    } else {
+                        for (int i = 0; e + i < total; ++i) out[e + i] = v[i];
+                    }
+                }
+            }
+        } else {
+            for (int uu = 0; uu < nu; ++uu) {
+                if (!((fit_units >> uu) & 1u) || !task_live) continue;
+                for (int e = lane; e < keep; e += kWave) out[uu * keep + e] = (int)rows[uu * keep + e];
+            }
         }
     }
 }
