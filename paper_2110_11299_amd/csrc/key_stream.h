@@ -1,7 +1,9 @@
-// The key stream shared by the fine-grained predictor kernels: approximate scores S~ = Q~ K~^T
-// (paper section 3.1) of 16 query rows against all keys of their head, 16 keys at a time, from the
-// int8 matrix cores, plus the few hand-written instructions that consume a score.  Device code
-// only; everything is internal to the translation unit that includes it.
+// The key streams of the streaming predictor and the threshold sweep: approximate scores
+// S~ = Q~ K~^T (paper section 3.1) of 16 selection units (query rows, or groups of rows whose scores
+// are summed: section 5.1) against all keys of their head, 16 keys at a time, from the int8 matrix
+// cores, in two forms (a wavefront on its own, straight from memory; four wavefronts of a workgroup
+// sharing the keys through LDS), plus the few hand-written instructions that consume a score.
+// Device code only; everything is internal to the translation unit that includes it.
 #pragma once
 
 #include "dsa_internal.h"

@@ -1,24 +1,30 @@
-// Fine-grained predictor in streaming form (paper section 3.1: approximate scores S~ = Q~ K~^T
-// and the per-row top-k that becomes the mask; section 3.4: the score contraction is cheap, "a
-// low-precision GEMM").  For vec = 1 the contraction is so cheap on the int8 matrix cores (7 us
-// for all of L = 4096, 16 heads) that it pays to compute it twice and never keep a score:
+// Predictor in streaming form (paper section 3.1: approximate scores S~ = Q~ K~^T and the per-unit
+// top-k that becomes the mask; section 3.4: the score contraction is cheap, "a low-precision GEMM";
+// section 5.1: a unit is a query row or a group of 4 / 8 rows whose scores are summed).  The
+// contraction is so cheap on the int8 matrix cores (7 us for all of L = 4096, 16 heads) that it pays
+// to compute it twice and never keep a score:
 //
-//   One wavefront owns 16 selection units (query rows) of one head and streams all L keys, with
-//   no other wavefront to wait for: no workgroup barrier anywhere.  Matrix-core orientation: keys
-//   are the rows (A operand), the 16 units the columns (B operand) of
-//   v_mfma_i32_16x16x{32,64}_i8.  Lane (c = lane % 16, g = lane / 16) receives, per tile, the
-//   scores of unit c against 4 consecutive keys of quarter g of the key range.  Every phase keeps
-//   that layout: the four lanes (c, 0..3) work for unit c, so all 16 units advance together in
-//   plain vector instructions, with no scalar bookkeeping and no serial chain per unit.
+//   One wavefront owns 16 selection units of one head and sweeps all L keys.  Four wavefronts with
+//   consecutive units of the same head form a workgroup and share the two sweeps: the keys are
+//   fetched once per workgroup and handed round through LDS (key_stream.h), one barrier per group
+//   of 8 tiles; everything between and after the sweeps is a wavefront's own business.
+//   Matrix-core orientation: keys are the rows (A operand), the 16 units the columns (B operand) of
+//   v_mfma_i32_16x16x64_i8.  Lane (c = lane % 16, g = lane / 16) receives, per tile, the scores of
+//   unit c against 4 consecutive keys of quarter g of the key range.  Every phase keeps that
+//   layout: the four lanes (c, 0..3) work for unit c, so all 16 units advance together in plain
+//   vector instructions, with no scalar bookkeeping and no serial chain per unit.
 //
-//   pass 1  stream the keys; every lane keeps NB maxima over disjoint key sets ("buckets", tile
+//   pass 1  sweep the keys; every lane keeps NB maxima over disjoint key sets ("buckets", tile
 //           t of a quarter belongs to bucket t % NB): half a vector operation per score.
 //   bound   T0 = the keep-th largest of a unit's 4*NB bucket maxima (a few more are accepted): at
-//           least keep keys reach T0, so T0 is a lower bound of the keep-th largest score.  Every
-//           unit bisects on the value, each lane counting its own maxima.
-//   pass 2  stream the keys again; compare every score with T0 and shift the outcome into a
-//           32-bit word (compare into carry, add with carry): the words are the unit's bitmap of
-//           candidate keys, in key order.
+//           least keep keys reach T0, so T0 is a lower bound of the keep-th largest score.  A
+//           histogram of the maxima in LDS narrows the range to one bin, a bisection on the value
+//           (each lane counting its own maxima) finishes inside it.
+//   pass 2  sweep the keys again with -T0 as the accumulator input: the sign of what comes out
+//           says whether the score reaches T0, and one funnel shift per score collects the signs
+//           in 32-bit words: the unit's bitmap of candidate keys, in key order.
+//   ties    units with too many candidates (plateaus of equal scores) are swept once more with
+//           T0 + 1; the bits that drop out are the ties, of which the first in key order are kept.
 //   list    every lane turns its words into key indices, appended to its unit's list in LDS at the
 //           offset its quarter starts at: the list is in key order.
 //   scores  the list is dealt out again in four equal runs, one per lane of the unit (whatever the
