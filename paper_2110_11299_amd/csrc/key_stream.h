@@ -251,12 +251,21 @@ template <int K, int VEC = 1> struct StagedKeyStream {
     __device__ __forceinline__ void restart(int b)
     {
         bias = v4i{b, b, b, b};
-        fetch(g[0], 0);
-        fetch(g[1], 1);
-        put(g[0], 0);
-        fetch(g[0], 2);
-        put(g[1], 1);
-        put(g[0], 2);
+        if (kDepth >= 3) {                      // the first three chunks in one round trip to memory
+            fetch(g[0], 0);
+            fetch(g[1], 1);
+            fetch(g[2 % kDepth], 2);
+            put(g[0], 0);
+            put(g[1], 1);
+            put(g[2 % kDepth], 2);
+        } else {
+            fetch(g[0], 0);
+            fetch(g[1], 1);
+            put(g[0], 0);
+            fetch(g[0], 2);
+            put(g[1], 1);
+            put(g[0], 2);
+        }
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) fetch(g[d], 3 + d);
         meet<0>();
