@@ -147,6 +147,31 @@ def test_mask_with_heavy_ties(dsa, oracle, vec, lo, hi):
         assert np.array_equal(idx.cpu().numpy().reshape(want.shape), want)
 
 
+@pytest.mark.parametrize("L,keep,vec", [(512, 51, 1), (256, 33, 1), (640, 45, 1), (2048, 103, 8), (1024, 61, 4)])
+def test_mask_with_zero_query_rows(dsa, oracle, L, keep, vec):
+    """Units whose projected query is all zero among ordinary ones: every score of such a unit is the same,
+    so any score read too early, or any word of its bitmap touched by a neighbour, shows in its list (the
+    first `keep` keys).  keep is chosen so that the image of the index rows is the larger part of a
+    wavefront's LDS and has an odd length; several launches, because such faults come and go."""
+    import torch
+    B, H, k = (8, 8, 32) if vec == 8 else (2, 6, 32)       # vec = 8: enough units for the streaming kernel
+    Qt, Kt = di.random_int8_case(900 + L, B, H, L, k)
+    Qt = Qt.copy()
+    for first in (0, 2, 15, 16 * 5 + 7):
+        Qt[:, :, first * vec::48 * vec] = 0
+        for r in range(1, vec):
+            Qt[:, :, first * vec + r::48 * vec] = 0
+    sh = dsa.make_shape(B, H, L, 64, k, keep, vec, dsa.DSA_F32, 0.125)
+    want = oracle.predict_mask(Qt, Kt, keep, vec)
+    q, kk = torch.from_numpy(Qt).cuda(), torch.from_numpy(Kt).cuda()
+    for launch in range(4):
+        print(f"[zero rows] L={L} keep={keep} vec={vec} launch {launch}", flush=True)
+        idx = dsa.dsa_predict_mask(sh, q, kk)
+        torch.cuda.synchronize()
+        bad = int((idx.cpu().numpy().reshape(want.shape) != want).any(axis=1).sum())
+        assert bad == 0, f"{bad} of {want.shape[0]} units differ in launch {launch}"
+
+
 @pytest.mark.parametrize("L", [4096, 2500])
 def test_mask_with_score_plateaus(dsa, oracle, L):
     """Scores that take three values only, on plateaus of several hundred keys: the kept set is
