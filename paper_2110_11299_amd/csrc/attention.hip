@@ -158,12 +158,12 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
     const unsigned n = r / (unsigned)L, i = r % (unsigned)L;
     const int32_t *list = idx + ((size_t)n * (L / vec) + i / vec) * keep;
     // per wavefront in LDS: the row's key list, as the byte offset of every key row inside its head
-    // (keys clamped into [0, L), so that no idx can send a gather outside K / V), and, in the fused
-    // mode, its scores, later its weights.  The list is padded to keep_pad, a multiple of the keys one
+    // (keys clamped into [0, L), so that no idx can send a gather outside K / V), and its scores, later
+    // (or from the start, when the weights are given) its weights.  The list is padded to keep_pad, a multiple of the keys one
     // trip of the loops below takes, with its last key: a padded entry has the score of a real one (no
     // effect on the maximum) and gets the weight 0, so the loops test nothing.
     constexpr unsigned kRowBytes = D * sizeof(T), kPieceBytes = E * sizeof(T);
-    unsigned *sl = reinterpret_cast<unsigned *>(lds_scores) + wave * (MODE == kFused ? 2 : 1) * keep_pad;
+    unsigned *sl = reinterpret_cast<unsigned *>(lds_scores) + wave * 2 * keep_pad;
     float *sc = reinterpret_cast<float *>(sl + keep_pad);
     unsigned *sw = reinterpret_cast<unsigned *>(sc);      // the same words once they hold weights
     for (int t = lane; t < keep_pad; t += kWave) sl[t] = (unsigned)min(max(list[min(t, keep - 1)], 0), L - 1) * kRowBytes;
@@ -195,18 +195,20 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
 #pragma unroll
             for (int u = 0; u < UU; ++u) {
                 const int t = t0 + u * RPI + grp;
-                if (MODE == kSddmm) {
-                    if (sub == 0 && live && t < keep) S[(size_t)r * keep + t] = acc[u] * factor;
-                } else {
-                    m = fmaxf(m, acc[u]);
-                    sc[t] = acc[u];           // every lane of the group writes the same value
-                }
+                if (MODE != kSddmm) m = fmaxf(m, acc[u]);
+                sc[t] = acc[u];               // every lane of the group writes the same value
             }
         };
         int t0 = 0;
         for (; t0 + U * RPI <= keep_pad; t0 += U * RPI) scores_of(t0, std::integral_constant<int, U>{});
         for (; t0 < keep_pad; t0 += RPI) scores_of(t0, std::integral_constant<int, 1>{});
-        if (MODE == kSddmm) return;
+        if (MODE == kSddmm) {
+            // the row of scores leaves in one piece: consecutive lanes, consecutive entries
+            wave_lds_fence();
+            if (live)
+                for (int t = lane; t < keep; t += kWave) S[(size_t)r * keep + t] = sc[t] * factor;
+            return;
+        }
         m = groups_max<LPR>(m);
         wave_lds_fence();
         // unnormalised weights, computed once per kept key (the lanes that share a value row would
@@ -215,6 +217,11 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
         wave_lds_fence();
     }
 
+    if (MODE == kSpmm) {
+        // the given weights come in the same way and wait in LDS in the form the products take them
+        for (int t = lane; t < keep_pad; t += kWave) sw[t] = t < keep ? P::weight(Pin[(size_t)r * keep + t]) : 0u;
+        wave_lds_fence();
+    }
     float o[E], z = 0.f;
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] = 0.f;
@@ -227,8 +234,7 @@ __global__ __launch_bounds__(kRowWaves *kWave) void attention_rows(
         for (int u = 0; u < UU; ++u) {
             const int t = t0 + u * RPI + grp;
             vv[u] = piece_of(Vh, sl[t]);
-            if (MODE == kSpmm) w[u] = t < keep ? P::weight(Pin[(size_t)r * keep + t]) : 0u;
-            else w[u] = sw[t];
+            w[u] = sw[t];
         }
 #pragma unroll
         for (int u = 0; u < UU; ++u) {
@@ -629,9 +635,9 @@ hipError_t launch_rows(AttnMode mode, const dsa_shape &sh, const void *Q, const 
 {
     const unsigned rows = (unsigned)sh.B * sh.H * sh.L;
     const dim3 grid((rows + kRowWaves - 1) / kRowWaves), block(kRowWaves * kWave);
-    // per wavefront: the padded key list, plus the scores in the fused mode
+    // per wavefront: the padded key list and the scores / weights
     const int keep_pad = (sh.keep + kRowPad - 1) / kRowPad * kRowPad;
-    const size_t lds = (size_t)kRowWaves * keep_pad * sizeof(float) * (mode == kFused ? 2 : 1);
+    const size_t lds = (size_t)kRowWaves * keep_pad * sizeof(float) * 2;
     const T *q = static_cast<const T *>(Q), *k = static_cast<const T *>(K), *v = static_cast<const T *>(V);
     if (mode == kFused) {
         auto kern = attention_rows<T, D, kFused>;
