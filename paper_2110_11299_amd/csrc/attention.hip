@@ -619,6 +619,32 @@ __global__ __launch_bounds__(kRowWaves *kWave) void softmax_rows(const float *S,
     if (row >= total_rows) return;
     const float *s = S + (size_t)row * keep;
     float *p = P + (size_t)row * keep;
+    constexpr int R = 8;                   // rows of up to 64 R entries stay in registers: read once, one exponential each
+    if (keep <= R * kWave) {
+        float v[R];
+        float m = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int t = lane + i * kWave;
+            v[i] = t < keep ? s[t] : -INFINITY;
+            m = fmaxf(m, v[i]);
+        }
+        m = wave_all_max(m);
+        float z = 0.f;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            v[i] = __expf(v[i] - m);      // exp(-inf) = 0 beyond the row
+            z += v[i];
+        }
+        z = wave_all_sum(z);
+        const float inv = 1.f / z;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int t = lane + i * kWave;
+            if (t < keep) p[t] = v[i] * inv;
+        }
+        return;
+    }
     float m = -INFINITY;
     for (int t = lane; t < keep; t += kWave) m = fmaxf(m, s[t]);
     m = wave_all_max(m);
