@@ -42,7 +42,9 @@ MUTANTS = [
     ("empty unit keeps the highest index among equals", "if (sc[j] > sc[best]) best = j;", "if (sc[j] >= sc[best]) best = j;"),
     ("empty unit keeps nothing", "if (count == 0) {\n                if (col) col[row_ptr[u]] = best;\n                count = 1;",
      "if (count < 0) {\n                if (col) col[row_ptr[u]] = best;\n                count = 1;"),
-    ("CSR row reads the next unit's keys", "const int32_t *list = col + row_ptr[u];", "const int32_t *list = col + row_ptr[u] + 1;"),
+    # (starts at the unit before: every read stays inside col, a planted mistake must not fault)
+    ("CSR row reads the keys of the unit before", "const int32_t *list = col + row_ptr[u];",
+     "const int32_t *list = col + row_ptr[u > 0 ? u - 1 : 0];"),
     ("CSR weights not normalised", "const double w = p[a] / z;", "const double w = p[a]; (void)z;"),
     ("ternary projection ignores the minus signs", "else if (sign < 0) y = y - X[r * d + c];", "else if (sign < 0) y = y + X[r * d + c];"),
     ("projection matrix transposed", "y = fmaf(X[r * d + c], R[(int64_t)c * k + j], y);",
